@@ -1,0 +1,120 @@
+"""The C oracle against what the definition and the mathematics fix (no GPU)."""
+import numpy as np
+import pytest
+
+import pins
+
+
+def oracle_impl(oracle_mod):
+    def impl(q, k, v, tables, lens, scale):
+        return oracle_mod.paged_attention_decode(q, k, v, tables, lens, scale, dtype="f64")
+    return impl
+
+
+@pytest.mark.parametrize("pin", pins.ALL_PINS, ids=lambda f: f.__name__)
+def test_oracle_attention_pin(oracle_mod, pin):
+    pin(oracle_impl(oracle_mod))
+
+
+def test_oracle_storage_dtypes_widen_exactly(oracle_mod):
+    """bf16 / f32 storage gives the same result as the same values handed over as f64."""
+    import kvc_workloads as W
+    p = pins.random_problem(5, nseq=3, hq=4, hkv=2, d=8, bs=4, max_ctx=19)
+    ref_f32 = oracle_mod.paged_attention_decode(
+        p["q"].astype(np.float32).astype(np.float64), p["k"].astype(np.float32).astype(np.float64),
+        p["v"].astype(np.float32).astype(np.float64), p["tables"], p["lens"], p["scale"], dtype="f64")
+    got_f32 = oracle_mod.paged_attention_decode(
+        p["q"].astype(np.float32), p["k"].astype(np.float32), p["v"].astype(np.float32),
+        p["tables"], p["lens"], p["scale"], dtype="f32")
+    assert np.array_equal(ref_f32, got_f32)
+    qb, kb, vb = (W.f32_to_bf16_bits(x.astype(np.float32)) for x in (p["q"], p["k"], p["v"]))
+    ref_bf = oracle_mod.paged_attention_decode(
+        W.to_float64(qb, "bf16"), W.to_float64(kb, "bf16"), W.to_float64(vb, "bf16"),
+        p["tables"], p["lens"], p["scale"], dtype="f64")
+    got_bf = oracle_mod.paged_attention_decode(qb, kb, vb, p["tables"], p["lens"], p["scale"],
+                                               dtype="bf16")
+    assert np.array_equal(ref_bf, got_bf)
+    # bf16 bit pattern 0x3FC0 is 1.5, 0xC000 is -2.0 (format definition)
+    assert W.bf16_bits_to_f32(np.array([0x3FC0, 0xC000], dtype=np.uint16)).tolist() == [1.5, -2.0]
+
+
+def test_oracle_row_subset_and_threads(oracle_mod):
+    p = pins.random_problem(6, nseq=4, hq=4, hkv=2, d=8, bs=4, max_ctx=25)
+    full = oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], p["lens"],
+                                             p["scale"], dtype="f64")
+    rows = [(0, 1), (3, 2), (2, 0)]
+    sub = oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], p["lens"],
+                                            p["scale"], dtype="f64", rows=rows)
+    for n, h in rows:
+        assert np.array_equal(sub[n, h], full[n, h])
+    assert np.isnan(sub[1]).all()
+    par = oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], p["lens"],
+                                            p["scale"], dtype="f64", num_threads=4)
+    assert np.array_equal(par, full)
+
+
+def test_oracle_rejects_block_ids_outside_pool(oracle_mod):
+    p = pins.random_problem(7, nseq=2, hq=2, hkv=1, d=4, bs=4, max_ctx=9)
+    p["tables"][0, 0] = p["k"].shape[0]
+    with pytest.raises(ValueError):
+        oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], p["lens"],
+                                          p["scale"], dtype="f64")
+
+
+# ----------------------------------------------------------------------------
+# block copy
+# ----------------------------------------------------------------------------
+def test_oracle_block_copy_matches_numpy_indexing(oracle_mod):
+    rng = np.random.default_rng(8)
+    src = rng.integers(0, 256, (3, 10, 48), dtype=np.uint8)
+    dst = rng.integers(0, 256, (3, 7, 48), dtype=np.uint8)
+    mapping = np.array([[9, 0], [2, 6], [2, 3], [5, 1]], dtype=np.int64)   # src 2 fans out
+    want = dst.copy()
+    want[:, mapping[:, 1]] = src[:, mapping[:, 0]]                         # numpy's own gather/scatter
+    oracle_mod.kv_block_copy(src, dst, mapping)
+    assert np.array_equal(dst, want)
+    untouched = [b for b in range(7) if b not in mapping[:, 1]]
+    assert len(untouched) == 3
+
+
+def test_oracle_block_copy_hand_case(oracle_mod):
+    """2 planes, 3 blocks of 2 bytes, hand-written expectation."""
+    src = np.array([[[1, 2], [3, 4], [5, 6]], [[11, 12], [13, 14], [15, 16]]], dtype=np.uint8)
+    dst = np.full((2, 2, 2), 99, dtype=np.uint8)
+    oracle_mod.kv_block_copy(src, dst, np.array([[2, 0]], dtype=np.int64))
+    assert dst.tolist() == [[[5, 6], [99, 99]], [[15, 16], [99, 99]]]
+
+
+def test_oracle_block_copy_empty_and_bad_ids(oracle_mod):
+    src = np.arange(24, dtype=np.uint8).reshape(1, 3, 8)
+    dst = np.zeros((1, 3, 8), dtype=np.uint8)
+    oracle_mod.kv_block_copy(src, dst, np.zeros((0, 2), dtype=np.int64))
+    assert not dst.any()
+    with pytest.raises(ValueError):
+        oracle_mod.kv_block_copy(src, dst, np.array([[3, 0]], dtype=np.int64))
+    with pytest.raises(ValueError):
+        oracle_mod.kv_block_copy(src, dst, np.array([[0, -1]], dtype=np.int64))
+    assert not dst.any()
+
+
+def test_oracle_swap_round_trip_restores_attention(oracle_mod):
+    """Swap a sequence's blocks out, poison them, swap back into other slots: same output bits."""
+    p = pins.random_problem(9, nseq=3, hq=4, hkv=2, d=8, bs=4, max_ctx=22, nb=40)
+    before = oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], p["lens"],
+                                               p["scale"], dtype="f64")
+    pool1 = np.stack([p["k"], p["v"]])                  # [2 planes][NB][Hkv][Bs][D]
+    pool2 = np.zeros((2, 12) + p["k"].shape[1:])
+    n = 1
+    nblk = (p["lens"][n] + 3) // 4
+    mine = p["tables"][n, :nblk].astype(np.int64)
+    used = set(int(b) for row, L in zip(p["tables"], p["lens"]) for b in row[:(L + 3) // 4])
+    free = np.array([b for b in range(40) if b not in used], dtype=np.int64)[:nblk]
+    slot2 = np.arange(nblk, dtype=np.int64)[::-1].copy()
+    oracle_mod.kv_block_copy(pool1, pool2, np.stack([mine, slot2], axis=1))
+    pool1[:, mine] = np.nan
+    oracle_mod.kv_block_copy(pool2, pool1, np.stack([slot2, free], axis=1))
+    tables = p["tables"].copy()
+    tables[n, :nblk] = free
+    after = oracle_mod.paged_attention_decode(p["q"], pool1[0], pool1[1], tables, p["lens"],
+                                              p["scale"], dtype="f64")
+    assert np.array_equal(before, after)
