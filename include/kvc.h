@@ -1,0 +1,193 @@
+/*
+ * kvc.h - C ABI of the paged-KV decode hot path for AMD MI355X (gfx950 / CDNA4).
+ *
+ * The paper's method (Sections 3.2-3.5) is host-side scheduling policy over a KV
+ * cache that is handed out in fixed-size token blocks (Section 1; Section 3.3.1:
+ * a request's blocks may sit anywhere in the pool, even inside another
+ * request's allocation).  Every iteration that policy pays for is a batched
+ * decode attention that reads each running request's whole KV through its
+ * block list (Section 3.3.2: iteration time grows with the tokens in the
+ * batch), and every preemption by swapping (Section 2.5, Section 3.5: cost
+ * linear in sequence length) or KV reuse is a copy of KV blocks.  This library
+ * is those two operations and nothing else.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE memory owned by the caller unless a comment
+ *     says "host".  Descriptor structs are host memory, read during the call only.
+ *   - The library allocates and frees nothing and never synchronises the stream;
+ *     work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns at once.  The kvc_validate_* calls are
+ *     the exception: they copy index arrays to the host and block.
+ *   - Return value: KVC_OK (0) or a negative kvc_status.  Host-visible arguments
+ *     are checked before anything is launched; on error nothing is written.
+ *   - Contents of device index arrays (block ids, context lengths, mappings) are
+ *     NOT checked on the fast path; out-of-range values there are undefined
+ *     behaviour.  Use kvc_validate_* when in doubt.
+ *
+ * Tensor layouts (row-major, last index fastest; T = float or bfloat16):
+ *   q, out        T [num_seqs][num_q_heads][head_dim]
+ *   k_cache       T [num_pool_blocks][num_kv_heads][block_size][head_dim]
+ *   v_cache       T [num_pool_blocks][num_kv_heads][block_size][head_dim]
+ *   block_tables  int32 [num_seqs][max_blocks_per_seq]
+ *   context_lens  int32 [num_seqs]
+ * Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ */
+#ifndef KVC_H
+#define KVC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported from libkvc_hip.so (the library is built with hidden default visibility) */
+#define KVC_API __attribute__((visibility("default")))
+
+typedef enum {
+    KVC_OK = 0,
+    KVC_ERR_NULL = -1,        /* a required pointer is NULL */
+    KVC_ERR_BAD_SHAPE = -2,   /* a size is non-positive or inconsistent */
+    KVC_ERR_BAD_DTYPE = -3,
+    KVC_ERR_UNSUPPORTED = -4, /* valid but not implemented (e.g. head_dim 96) */
+    KVC_ERR_WORKSPACE = -5,   /* workspace NULL or too small */
+    KVC_ERR_ALIGN = -6,       /* pointer / stride not 16-byte aligned */
+    KVC_ERR_LAUNCH = -7,      /* HIP reported an error; see kvc_last_hip_error */
+    KVC_ERR_BAD_INDEX = -8,   /* kvc_validate_*: an index is out of range */
+    KVC_ERR_DUPLICATE = -9,   /* kvc_validate_*: a destination block appears twice */
+    KVC_ERR_OVERLAP = -10     /* kvc_validate_*: same pool, source and destination sets meet */
+} kvc_status;
+
+typedef enum { KVC_F32 = 0, KVC_BF16 = 1 } kvc_dtype;
+
+/* Which partial kernel computes the attention (KVC_KERNEL_AUTO picks). */
+typedef enum {
+    KVC_KERNEL_AUTO = 0,
+    KVC_KERNEL_VALU = 1, /* vector-ALU dot products; any supported shape */
+    KVC_KERNEL_MFMA = 2, /* matrix-core tiles; bf16, head_dim 128, block_size % 16 == 0, group <= 16;
+                            K tiles go from HBM straight into the MFMA operand layout */
+    KVC_KERNEL_MFMA_LDS = 3 /* same, K tiles loaded fully coalesced and re-laid-out through LDS */
+} kvc_kernel;
+
+typedef struct {
+    int32_t num_seqs;           /* >= 0 (0 is a no-op) */
+    int32_t num_q_heads;        /* multiple of num_kv_heads */
+    int32_t num_kv_heads;
+    int32_t head_dim;           /* 64 or 128 */
+    int32_t block_size;         /* tokens per block: a power of two, 1..256 */
+    int32_t max_blocks_per_seq; /* row length of block_tables */
+    int32_t num_pool_blocks;    /* blocks in k_cache / v_cache (bounds for validation) */
+    int32_t dtype;              /* kvc_dtype of q, k_cache, v_cache and out */
+    int32_t max_context_len;    /* host-known upper bound on context_lens; 0 means
+                                   max_blocks_per_seq * block_size.  A tight bound keeps
+                                   the launch grid and the workspace small. */
+    int32_t partition_tokens;   /* split-K partition length in tokens (multiple of 16);
+                                   0 lets the library choose */
+    int32_t kernel;             /* kvc_kernel */
+    int32_t reserved;           /* must be 0 */
+} kvc_attn_desc;
+
+/* What the library will do for a descriptor (filled by kvc_attn_plan). */
+typedef struct {
+    int32_t kernel;            /* the kvc_kernel that will run (never AUTO) */
+    int32_t partition_tokens;
+    int32_t max_partitions;    /* partitions per sequence the grid provides for */
+    int32_t partial_grid;      /* workgroups of the partial kernel */
+    int32_t merge_grid;        /* workgroups of the merge kernel (0: not launched) */
+    int32_t reserved;
+    uint64_t workspace_bytes;
+} kvc_attn_plan_info;
+
+KVC_API int kvc_version(void);
+KVC_API const char *kvc_status_string(int status);
+/* hipError_t of the last failed HIP call made by this thread inside the library (0 if none). */
+KVC_API int kvc_last_hip_error(void);
+
+/* Checks `desc` (host) and reports kernel choice, grid and workspace.  No GPU needed. */
+KVC_API int kvc_attn_plan(const kvc_attn_desc *desc, kvc_attn_plan_info *plan);
+
+/* Bytes of device workspace kvc_paged_attention_decode needs for `desc`
+ * (0 when no sequence can span more than one partition, or on a bad desc). */
+KVC_API size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *desc);
+
+/*
+ * Batched single-token attention over a block-allocated KV cache:
+ *   out[n][h][:] = sum_t softmax_t( scale * q[n][h] . K[n,t] ) * V[n,t],  t < context_lens[n],
+ * where token t of sequence n lives in block block_tables[n][t / block_size], slot
+ * t % block_size, KV head h / group.  (Decode step of an iteration-level scheduler over
+ * block-based KV allocation: Section 1, Section 3.1, Section 3.3.)
+ *
+ *   - Table entries at index >= ceil(context_len / block_size) are never dereferenced, and
+ *     pool contents at slots >= context_len in the last block never reach `out` (NaN there
+ *     is fine).  One block id may appear in many rows (shared prefix).
+ *   - context_lens[n] == 0 writes a row of zeros.
+ *   - Accumulation is fp32; bf16 output is rounded to nearest even.
+ *   - Two launches: a split-K partial kernel over (sequence, kv head, partition) and a merge
+ *     kernel; a sequence that fits one partition is finished by the first.
+ *   - `workspace`: device memory, 256-byte aligned, at least
+ *     kvc_paged_attention_decode_workspace_bytes(desc); may be NULL when that is 0.  It is
+ *     scratch: contents before and after the call are meaningless.
+ *   - q, k_cache, v_cache, out must be 16-byte aligned.
+ */
+KVC_API int kvc_paged_attention_decode(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               float scale, void *out, const kvc_attn_desc *desc,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The two launches of kvc_paged_attention_decode on their own (same arguments, same
+ * checks), for callers that time or schedule them separately.  Running partial then
+ * merge on one stream equals kvc_paged_attention_decode. */
+KVC_API int kvc_paged_attention_decode_partial(const void *q, const void *k_cache, const void *v_cache,
+                                       const int32_t *block_tables, const int32_t *context_lens,
+                                       float scale, void *out, const kvc_attn_desc *desc,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+KVC_API int kvc_paged_attention_decode_merge(const int32_t *context_lens, void *out,
+                                     const kvc_attn_desc *desc, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream);
+
+/* Blocking check of the device index arrays against `desc`: 0 <= context_lens[n] <=
+ * min(max_context_len, max_blocks_per_seq * block_size) and every dereferenced table entry in
+ * [0, num_pool_blocks).  Returns KVC_ERR_BAD_INDEX on the first violation. */
+KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int32_t *context_lens,
+                                  const kvc_attn_desc *desc, void *hip_stream);
+
+/*
+ * A KV pool as the copy sees it: num_planes planes (K or V of one layer each) of num_blocks
+ * blocks of block_bytes bytes; plane p starts at base + p * plane_stride_bytes.
+ */
+typedef struct {
+    void *base;                 /* device, 16-byte aligned */
+    int64_t num_blocks;
+    int64_t block_bytes;        /* multiple of 16 */
+    int64_t plane_stride_bytes; /* multiple of 16, >= num_blocks * block_bytes (ignored if num_planes == 1) */
+    int32_t num_planes;         /* >= 1 */
+    int32_t reserved;           /* must be 0 */
+} kvc_pool;
+
+/*
+ * Block gather/scatter between KV pools, bit-exact: for every pair (s, d) of
+ * block_mapping and every plane p, dst[p][d][:] = src[p][s][:].  This is the data
+ * movement behind swapping a preempted request's KV out and back in (Section 2.5,
+ * Section 3.5) and behind relocating blocks for KV reuse (Section 3.3.1).
+ *
+ *   - block_mapping: device int64 [num_pairs][2] = (src_block, dst_block); num_pairs may be 0.
+ *   - src and dst must agree in block_bytes and num_planes; num_blocks may differ.
+ *   - A source block may appear several times (fan-out).  A destination block must appear at
+ *     most once, and when src and dst are the same memory the source and destination block
+ *     sets must be disjoint; neither is checked here (see kvc_validate_block_mapping).
+ *   - Blocks of dst that are not a destination are left untouched.
+ */
+KVC_API int kvc_kv_block_copy(const kvc_pool *src, const kvc_pool *dst, const int64_t *block_mapping,
+                      int64_t num_pairs, void *hip_stream);
+
+/* Blocking check of a device block_mapping: ids in range (KVC_ERR_BAD_INDEX), no duplicate
+ * destination (KVC_ERR_DUPLICATE), and no source/destination overlap when the pools share
+ * memory (KVC_ERR_OVERLAP). */
+KVC_API int kvc_validate_block_mapping(const kvc_pool *src, const kvc_pool *dst,
+                               const int64_t *block_mapping, int64_t num_pairs, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVC_H */

@@ -1,0 +1,228 @@
+"""ctypes binding of the C ABI in include/kvc.h (same names, argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # device memory and streams; also makes sure one HIP runtime is shared
+
+KVC_F32, KVC_BF16 = 0, 1
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS = 0, 1, 2, 3
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libkvc_hip.so")
+_lib = None
+
+
+class KvcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status}, hip error "
+                         f"{lib().kvc_last_hip_error()})")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "block_size",
+        "max_blocks_per_seq", "num_pool_blocks", "dtype", "max_context_len",
+        "partition_tokens", "kernel", "reserved")]
+
+
+class AttnPlan(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("partition_tokens", ctypes.c_int32),
+                ("max_partitions", ctypes.c_int32), ("partial_grid", ctypes.c_int32),
+                ("merge_grid", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("workspace_bytes", ctypes.c_uint64)]
+
+
+class Pool(ctypes.Structure):
+    _fields_ = [("base", ctypes.c_void_p), ("num_blocks", ctypes.c_int64),
+                ("block_bytes", ctypes.c_int64), ("plane_stride_bytes", ctypes.c_int64),
+                ("num_planes", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Load libkvc_hip.so (built in-tree by paper_2503_13773_amd.build).  No fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: run `python -m paper_2503_13773_amd.build` "
+                           "(there is no CPU fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32p, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+    dp = ctypes.POINTER(AttnDesc)
+    pp = ctypes.POINTER(Pool)
+    L.kvc_version.restype = ctypes.c_int
+    L.kvc_status_string.restype = ctypes.c_char_p
+    L.kvc_status_string.argtypes = [ctypes.c_int]
+    L.kvc_last_hip_error.restype = ctypes.c_int
+    L.kvc_attn_plan.restype = ctypes.c_int
+    L.kvc_attn_plan.argtypes = [dp, ctypes.POINTER(AttnPlan)]
+    L.kvc_paged_attention_decode_workspace_bytes.restype = sz
+    L.kvc_paged_attention_decode_workspace_bytes.argtypes = [dp]
+    for name in ("kvc_paged_attention_decode", "kvc_paged_attention_decode_partial"):
+        fn = getattr(L, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp, sz, vp]
+    L.kvc_paged_attention_decode_merge.restype = ctypes.c_int
+    L.kvc_paged_attention_decode_merge.argtypes = [i32p, vp, dp, vp, sz, vp]
+    L.kvc_validate_attention_inputs.restype = ctypes.c_int
+    L.kvc_validate_attention_inputs.argtypes = [i32p, i32p, dp, vp]
+    L.kvc_kv_block_copy.restype = ctypes.c_int
+    L.kvc_kv_block_copy.argtypes = [pp, pp, vp, ctypes.c_int64, vp]
+    L.kvc_validate_block_mapping.restype = ctypes.c_int
+    L.kvc_validate_block_mapping.argtypes = [pp, pp, vp, ctypes.c_int64, vp]
+    _lib = L
+    return L
+
+
+def version() -> int:
+    return int(lib().kvc_version())
+
+
+def status_string(status: int) -> str:
+    return lib().kvc_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise KvcError(status, where)
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return KVC_F32
+    if t.dtype == torch.bfloat16:
+        return KVC_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def attn_desc(q, k_cache, block_tables, *, max_context_len: int = 0, partition_tokens: int = 0,
+              kernel: int = KERNEL_AUTO) -> AttnDesc:
+    """Describe the shapes of a decode call from its tensors."""
+    nseq, hq, d = q.shape
+    nb, hkv, bs, d2 = k_cache.shape
+    if d2 != d:
+        raise ValueError("head_dim of q and k_cache differ")
+    return AttnDesc(num_seqs=nseq, num_q_heads=hq, num_kv_heads=hkv, head_dim=d, block_size=bs,
+                    max_blocks_per_seq=block_tables.shape[1], num_pool_blocks=nb,
+                    dtype=_dtype_code(q), max_context_len=int(max_context_len),
+                    partition_tokens=int(partition_tokens), kernel=int(kernel), reserved=0)
+
+
+def attn_plan(desc: AttnDesc) -> AttnPlan:
+    plan = AttnPlan()
+    _check(lib().kvc_attn_plan(ctypes.byref(desc), ctypes.byref(plan)), "kvc_attn_plan")
+    return plan
+
+
+def workspace_bytes(desc: AttnDesc) -> int:
+    return int(lib().kvc_paged_attention_decode_workspace_bytes(ctypes.byref(desc)))
+
+
+def _attn_args(q, k_cache, v_cache, block_tables, context_lens, out, desc, workspace):
+    for t in (q, k_cache, v_cache, block_tables, context_lens):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    if v_cache.shape != k_cache.shape or v_cache.dtype != q.dtype or k_cache.dtype != q.dtype:
+        raise ValueError("k_cache / v_cache must match each other and q's dtype")
+    if block_tables.dtype != torch.int32 or context_lens.dtype != torch.int32:
+        raise TypeError("block_tables and context_lens must be int32")
+    if block_tables.shape[0] != q.shape[0] or context_lens.shape != (q.shape[0],):
+        raise ValueError("block_tables / context_lens do not match the batch")
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must look like q")
+    need = workspace_bytes(desc)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    return out, workspace, ws_ptr, ws_len
+
+
+def paged_attention_decode(q, k_cache, v_cache, block_tables, context_lens, scale: float,
+                           out=None, *, desc: Optional[AttnDesc] = None, max_context_len: int = 0,
+                           partition_tokens: int = 0, kernel: int = KERNEL_AUTO, workspace=None,
+                           stream=None):
+    """out[n,h] = softmax(scale * q[n,h] . K[n]) V[n] over each sequence's block list."""
+    if desc is None:
+        desc = attn_desc(q, k_cache, block_tables, max_context_len=max_context_len,
+                         partition_tokens=partition_tokens, kernel=kernel)
+    out, workspace, ws_ptr, ws_len = _attn_args(q, k_cache, v_cache, block_tables, context_lens,
+                                                out, desc, workspace)
+    _check(lib().kvc_paged_attention_decode(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
+        context_lens.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc), ws_ptr, ws_len,
+        _stream_handle(stream)), "kvc_paged_attention_decode")
+    return out
+
+
+def paged_attention_decode_partial(q, k_cache, v_cache, block_tables, context_lens, scale: float,
+                                   out, desc: AttnDesc, workspace, stream=None):
+    out, workspace, ws_ptr, ws_len = _attn_args(q, k_cache, v_cache, block_tables, context_lens,
+                                                out, desc, workspace)
+    _check(lib().kvc_paged_attention_decode_partial(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
+        context_lens.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc), ws_ptr, ws_len,
+        _stream_handle(stream)), "kvc_paged_attention_decode_partial")
+    return out
+
+
+def paged_attention_decode_merge(context_lens, out, desc: AttnDesc, workspace, stream=None):
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().kvc_paged_attention_decode_merge(
+        context_lens.data_ptr(), out.data_ptr(), ctypes.byref(desc), ws_ptr, ws_len,
+        _stream_handle(stream)), "kvc_paged_attention_decode_merge")
+    return out
+
+
+def validate_attention_inputs(block_tables, context_lens, desc: AttnDesc, stream=None) -> int:
+    """Blocking range check of the index arrays; returns the status (0 = fine)."""
+    return int(lib().kvc_validate_attention_inputs(block_tables.data_ptr(), context_lens.data_ptr(),
+                                                   ctypes.byref(desc), _stream_handle(stream)))
+
+
+def pool_of(t: torch.Tensor) -> Pool:
+    """View a tensor shaped [num_planes][num_blocks][...] as a kvc_pool."""
+    if not t.is_cuda or not t.is_contiguous() or t.dim() < 3:
+        raise ValueError("pool tensor must be a contiguous device tensor [planes][blocks][...]")
+    block_bytes = t[0, 0].numel() * t.element_size()
+    return Pool(base=t.data_ptr(), num_blocks=t.shape[1], block_bytes=block_bytes,
+                plane_stride_bytes=t.shape[1] * block_bytes, num_planes=t.shape[0], reserved=0)
+
+
+def kv_block_copy(src_pool, dst_pool, block_mapping, stream=None) -> None:
+    """dst[p][d] = src[p][s] for every (s, d) in block_mapping (device int64 [n][2]).
+
+    Pools are Pool structs or tensors shaped [num_planes][num_blocks][...].
+    """
+    src = src_pool if isinstance(src_pool, Pool) else pool_of(src_pool)
+    dst = dst_pool if isinstance(dst_pool, Pool) else pool_of(dst_pool)
+    if block_mapping.dtype != torch.int64 or not block_mapping.is_cuda or not block_mapping.is_contiguous():
+        raise TypeError("block_mapping must be a contiguous device int64 tensor [n][2]")
+    n = block_mapping.numel() // 2
+    _check(lib().kvc_kv_block_copy(ctypes.byref(src), ctypes.byref(dst), block_mapping.data_ptr(), n,
+                                   _stream_handle(stream)), "kvc_kv_block_copy")
+
+
+def validate_block_mapping(src_pool, dst_pool, block_mapping, stream=None) -> int:
+    src = src_pool if isinstance(src_pool, Pool) else pool_of(src_pool)
+    dst = dst_pool if isinstance(dst_pool, Pool) else pool_of(dst_pool)
+    n = block_mapping.numel() // 2
+    return int(lib().kvc_validate_block_mapping(ctypes.byref(src), ctypes.byref(dst),
+                                                block_mapping.data_ptr(), n, _stream_handle(stream)))

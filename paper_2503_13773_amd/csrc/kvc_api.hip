@@ -1,0 +1,355 @@
+// C ABI of libkvc_hip.so: argument checks, launch planning, kernel launches.
+// The contract of every entry point is stated in include/kvc.h.
+#include <math.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "kvc_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_failed(hipError_t e) {
+    g_last_hip_error = int(e);
+    return KVC_ERR_LAUNCH;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+constexpr int kMaxPartitionTokens = 4096;  // 4 wavefronts x 64 table entries x 16 tokens
+constexpr int64_t kMaxGrid = 0x7fffffff;
+
+struct Plan {
+    int kernel;
+    int partition_tokens;
+    int max_partitions;
+    int64_t partial_grid;
+    int64_t merge_grid;
+    uint64_t acc_bytes;  // offset of the (max, sum) array inside the workspace
+    uint64_t workspace_bytes;
+    int max_context_len;
+};
+
+bool mfma_ok(const kvc_attn_desc &d) {
+    return d.dtype == KVC_BF16 && d.head_dim == 128 && d.block_size >= 16 &&
+           d.num_q_heads / d.num_kv_heads <= 16;
+}
+
+int make_plan(const kvc_attn_desc *d, Plan *pl) {
+    if (!d) return KVC_ERR_NULL;
+    if (d->num_seqs < 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->head_dim <= 0 ||
+        d->block_size <= 0 || d->max_blocks_per_seq <= 0 || d->num_pool_blocks <= 0 ||
+        d->max_context_len < 0 || d->partition_tokens < 0 || d->reserved != 0)
+        return KVC_ERR_BAD_SHAPE;
+    if (d->num_q_heads % d->num_kv_heads != 0) return KVC_ERR_BAD_SHAPE;
+    if (d->dtype != KVC_F32 && d->dtype != KVC_BF16) return KVC_ERR_BAD_DTYPE;
+    if (d->head_dim != 64 && d->head_dim != 128) return KVC_ERR_UNSUPPORTED;
+    if (!is_pow2(d->block_size) || d->block_size > 256) return KVC_ERR_UNSUPPORTED;
+    const int64_t table_tokens = int64_t(d->max_blocks_per_seq) * d->block_size;
+    if (table_tokens > 0x40000000) return KVC_ERR_BAD_SHAPE;
+    if (d->max_context_len > table_tokens) return KVC_ERR_BAD_SHAPE;
+    const int max_ctx = d->max_context_len ? d->max_context_len : int(table_tokens);
+    if (d->partition_tokens % 16 != 0 || d->partition_tokens > kMaxPartitionTokens)
+        return KVC_ERR_BAD_SHAPE;
+
+    int kernel = d->kernel;
+    if (kernel < KVC_KERNEL_AUTO || kernel > KVC_KERNEL_MFMA_LDS) return KVC_ERR_BAD_SHAPE;
+    if (kernel == KVC_KERNEL_AUTO) kernel = mfma_ok(*d) ? KVC_KERNEL_MFMA : KVC_KERNEL_VALU;
+    if (kernel != KVC_KERNEL_VALU && !mfma_ok(*d)) return KVC_ERR_UNSUPPORTED;
+
+    const int group = d->num_q_heads / d->num_kv_heads;
+    const int64_t base_items = kernel == KVC_KERNEL_VALU
+                                   ? int64_t(d->num_seqs) * (d->num_q_heads / kvc::valu_head_chunk(group))
+                                   : int64_t(d->num_seqs) * d->num_kv_heads;
+    int pt = d->partition_tokens;
+    if (pt == 0) {
+        // Short partitions spread a skewed length mix over the 256 CUs; longer ones keep the
+        // grid (mostly idle workgroups when max_context_len is loose) and the workspace small.
+        if (max_ctx <= 256) {
+            pt = int(ceil_div(max_ctx, 16) * 16);
+        } else {
+            pt = 256;
+            while (pt < kMaxPartitionTokens && base_items * ceil_div(max_ctx, pt) > 16384) pt *= 2;
+        }
+    }
+    const int64_t parts = ceil_div(max_ctx, pt);
+    const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;
+    if (base_items * parts > kMaxGrid || rows * parts > kMaxGrid) return KVC_ERR_BAD_SHAPE;
+
+    pl->kernel = kernel;
+    pl->partition_tokens = pt;
+    pl->max_partitions = int(parts);
+    pl->partial_grid = base_items * parts;
+    pl->merge_grid = parts > 1 ? ceil_div(rows, kvc::kWaves) : 0;
+    pl->max_context_len = max_ctx;
+    if (parts > 1) {
+        const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);
+        pl->acc_bytes = (acc + 255) & ~uint64_t(255);
+        pl->workspace_bytes = pl->acc_bytes + uint64_t(rows) * parts * 2 * sizeof(float);
+    } else {
+        pl->acc_bytes = 0;
+        pl->workspace_bytes = 0;
+    }
+    return KVC_OK;
+}
+
+kvc::AttnParams make_params(const kvc_attn_desc &d, const Plan &pl, float scale) {
+    kvc::AttnParams p;
+    p.num_seqs = d.num_seqs;
+    p.num_q_heads = d.num_q_heads;
+    p.num_kv_heads = d.num_kv_heads;
+    p.group = d.num_q_heads / d.num_kv_heads;
+    p.block_size = d.block_size;
+    p.block_size_log2 = ilog2(d.block_size);
+    p.max_blocks_per_seq = d.max_blocks_per_seq;
+    p.partition_tokens = pl.partition_tokens;
+    p.max_partitions = pl.max_partitions;
+    p.k_via_lds = pl.kernel == KVC_KERNEL_MFMA_LDS;
+    p.scale = scale;
+    p.scale_log2e = float(double(scale) * 1.4426950408889634);
+    return p;
+}
+
+int check_workspace(const Plan &pl, void *workspace, size_t workspace_bytes, kvc::Workspace *ws) {
+    ws->acc = nullptr;
+    ws->ml = nullptr;
+    if (pl.workspace_bytes == 0) return KVC_OK;
+    if (!workspace || workspace_bytes < pl.workspace_bytes) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
+    ws->acc = static_cast<float *>(workspace);
+    ws->ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.acc_bytes);
+    return KVC_OK;
+}
+
+int run_partial(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                const int32_t *context_lens, float scale, void *out, const kvc_attn_desc *desc,
+                const Plan &pl, kvc::Workspace ws, hipStream_t stream) {
+    const kvc::AttnParams p = make_params(*desc, pl, scale);
+    hipError_t e;
+    if (pl.kernel == KVC_KERNEL_VALU)
+        e = kvc::launch_partial_valu(q, k_cache, v_cache, block_tables, context_lens, out, ws, p,
+                                     desc->dtype, desc->head_dim, int(pl.partial_grid), stream);
+    else
+        e = kvc::launch_partial_mfma(q, k_cache, v_cache, block_tables, context_lens, out, ws, p,
+                                     int(pl.partial_grid), stream);
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
+int run_merge(const int32_t *context_lens, void *out, const kvc_attn_desc *desc, const Plan &pl,
+              kvc::Workspace ws, hipStream_t stream) {
+    if (pl.merge_grid == 0) return KVC_OK;
+    const kvc::AttnParams p = make_params(*desc, pl, 1.0f);
+    const hipError_t e = kvc::launch_merge(context_lens, out, ws, p, desc->dtype, desc->head_dim,
+                                           pl.kernel != KVC_KERNEL_VALU, int(pl.merge_grid), stream);
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
+int check_attn_args(const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *block_tables, const int32_t *context_lens, float scale,
+                    const void *out) {
+    if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out) return KVC_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+        return KVC_ERR_ALIGN;
+    if (!isfinite(scale)) return KVC_ERR_BAD_SHAPE;
+    return KVC_OK;
+}
+
+int check_pools(const kvc_pool *src, const kvc_pool *dst, const int64_t *mapping, int64_t num_pairs) {
+    if (!src || !dst) return KVC_ERR_NULL;
+    if (num_pairs < 0) return KVC_ERR_BAD_SHAPE;
+    for (const kvc_pool *pl : {src, dst}) {
+        if (pl->num_blocks <= 0 || pl->block_bytes <= 0 || pl->num_planes <= 0 || pl->reserved != 0)
+            return KVC_ERR_BAD_SHAPE;
+        if (pl->num_planes > 65535) return KVC_ERR_UNSUPPORTED;
+        if (pl->block_bytes % 16 != 0) return KVC_ERR_ALIGN;
+        if (pl->num_planes > 1) {
+            if (pl->plane_stride_bytes % 16 != 0) return KVC_ERR_ALIGN;
+            if (pl->plane_stride_bytes / pl->block_bytes < pl->num_blocks) return KVC_ERR_BAD_SHAPE;
+        }
+    }
+    if (src->block_bytes != dst->block_bytes || src->num_planes != dst->num_planes)
+        return KVC_ERR_BAD_SHAPE;
+    if (num_pairs == 0) return KVC_OK;
+    if (!src->base || !dst->base || !mapping) return KVC_ERR_NULL;
+    if (!aligned16(src->base) || !aligned16(dst->base)) return KVC_ERR_ALIGN;
+    const int64_t slabs = ceil_div(src->block_bytes, int64_t(kvc::kThreads) * 64);
+    if (num_pairs > kMaxGrid / slabs) return KVC_ERR_BAD_SHAPE;
+    return KVC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvc_version(void) { return 100; }
+
+const char *kvc_status_string(int status) {
+    switch (status) {
+        case KVC_OK: return "ok";
+        case KVC_ERR_NULL: return "a required pointer is NULL";
+        case KVC_ERR_BAD_SHAPE: return "a size is non-positive or inconsistent";
+        case KVC_ERR_BAD_DTYPE: return "unknown dtype";
+        case KVC_ERR_UNSUPPORTED: return "shape or option not implemented";
+        case KVC_ERR_WORKSPACE: return "workspace missing or too small";
+        case KVC_ERR_ALIGN: return "pointer or stride not aligned";
+        case KVC_ERR_LAUNCH: return "HIP call failed (see kvc_last_hip_error)";
+        case KVC_ERR_BAD_INDEX: return "index out of range";
+        case KVC_ERR_DUPLICATE: return "destination block listed twice";
+        case KVC_ERR_OVERLAP: return "source and destination blocks overlap in one pool";
+        default: return "unknown status";
+    }
+}
+
+int kvc_last_hip_error(void) { return g_last_hip_error; }
+
+int kvc_attn_plan(const kvc_attn_desc *desc, kvc_attn_plan_info *plan) {
+    if (!plan) return KVC_ERR_NULL;
+    Plan pl;
+    const int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    plan->kernel = pl.kernel;
+    plan->partition_tokens = pl.partition_tokens;
+    plan->max_partitions = pl.max_partitions;
+    plan->partial_grid = int32_t(pl.partial_grid);
+    plan->merge_grid = int32_t(pl.merge_grid);
+    plan->reserved = 0;
+    plan->workspace_bytes = pl.workspace_bytes;
+    return KVC_OK;
+}
+
+size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *desc) {
+    Plan pl;
+    return make_plan(desc, &pl) == KVC_OK ? size_t(pl.workspace_bytes) : 0;
+}
+
+int kvc_paged_attention_decode_partial(const void *q, const void *k_cache, const void *v_cache,
+                                       const int32_t *block_tables, const int32_t *context_lens,
+                                       float scale, void *out, const kvc_attn_desc *desc,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (desc->num_seqs == 0) return KVC_OK;
+    rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
+    if (rc != KVC_OK) return rc;
+    kvc::Workspace ws;
+    rc = check_workspace(pl, workspace, workspace_bytes, &ws);
+    if (rc != KVC_OK) return rc;
+    return run_partial(q, k_cache, v_cache, block_tables, context_lens, scale, out, desc, pl, ws,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int kvc_paged_attention_decode_merge(const int32_t *context_lens, void *out,
+                                     const kvc_attn_desc *desc, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (desc->num_seqs == 0) return KVC_OK;
+    if (!context_lens || !out) return KVC_ERR_NULL;
+    if (!aligned16(out)) return KVC_ERR_ALIGN;
+    kvc::Workspace ws;
+    rc = check_workspace(pl, workspace, workspace_bytes, &ws);
+    if (rc != KVC_OK) return rc;
+    return run_merge(context_lens, out, desc, pl, ws, static_cast<hipStream_t>(hip_stream));
+}
+
+int kvc_paged_attention_decode(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               float scale, void *out, const kvc_attn_desc *desc, void *workspace,
+                               size_t workspace_bytes, void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (desc->num_seqs == 0) return KVC_OK;
+    rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
+    if (rc != KVC_OK) return rc;
+    kvc::Workspace ws;
+    rc = check_workspace(pl, workspace, workspace_bytes, &ws);
+    if (rc != KVC_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = run_partial(q, k_cache, v_cache, block_tables, context_lens, scale, out, desc, pl, ws, stream);
+    if (rc != KVC_OK) return rc;
+    return run_merge(context_lens, out, desc, pl, ws, stream);
+}
+
+int kvc_validate_attention_inputs(const int32_t *block_tables, const int32_t *context_lens,
+                                  const kvc_attn_desc *desc, void *hip_stream) {
+    Plan pl;
+    const int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (desc->num_seqs == 0) return KVC_OK;
+    if (!block_tables || !context_lens) return KVC_ERR_NULL;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<int32_t> lens(desc->num_seqs);
+    std::vector<int32_t> tables(size_t(desc->num_seqs) * desc->max_blocks_per_seq);
+    hipError_t e = hipMemcpyAsync(lens.data(), context_lens, lens.size() * sizeof(int32_t),
+                                  hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(tables.data(), block_tables, tables.size() * sizeof(int32_t),
+                           hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_failed(e);
+    for (int n = 0; n < desc->num_seqs; ++n) {
+        if (lens[n] < 0 || lens[n] > pl.max_context_len) return KVC_ERR_BAD_INDEX;
+        const int nblk = int(ceil_div(lens[n], desc->block_size));
+        for (int b = 0; b < nblk; ++b) {
+            const int32_t id = tables[size_t(n) * desc->max_blocks_per_seq + b];
+            if (id < 0 || id >= desc->num_pool_blocks) return KVC_ERR_BAD_INDEX;
+        }
+    }
+    return KVC_OK;
+}
+
+int kvc_kv_block_copy(const kvc_pool *src, const kvc_pool *dst, const int64_t *block_mapping,
+                      int64_t num_pairs, void *hip_stream) {
+    const int rc = check_pools(src, dst, block_mapping, num_pairs);
+    if (rc != KVC_OK) return rc;
+    if (num_pairs == 0) return KVC_OK;
+    const hipError_t e = kvc::launch_block_copy(*src, *dst, block_mapping, num_pairs,
+                                                static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
+int kvc_validate_block_mapping(const kvc_pool *src, const kvc_pool *dst,
+                               const int64_t *block_mapping, int64_t num_pairs, void *hip_stream) {
+    const int rc = check_pools(src, dst, block_mapping, num_pairs);
+    if (rc != KVC_OK) return rc;
+    if (num_pairs == 0) return KVC_OK;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<int64_t> map(size_t(num_pairs) * 2);
+    hipError_t e = hipMemcpyAsync(map.data(), block_mapping, map.size() * sizeof(int64_t),
+                                  hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_failed(e);
+    std::vector<int64_t> srcs(num_pairs), dsts(num_pairs);
+    for (int64_t i = 0; i < num_pairs; ++i) {
+        srcs[i] = map[2 * i];
+        dsts[i] = map[2 * i + 1];
+        if (srcs[i] < 0 || srcs[i] >= src->num_blocks || dsts[i] < 0 || dsts[i] >= dst->num_blocks)
+            return KVC_ERR_BAD_INDEX;
+    }
+    std::sort(dsts.begin(), dsts.end());
+    if (std::adjacent_find(dsts.begin(), dsts.end()) != dsts.end()) return KVC_ERR_DUPLICATE;
+    // Pools that share memory: a block that is both read and written would race.
+    const auto *sb = static_cast<const unsigned char *>(src->base);
+    const auto *db = static_cast<const unsigned char *>(dst->base);
+    const int64_t s_extent = (src->num_planes > 1 ? (src->num_planes - 1) * src->plane_stride_bytes : 0) +
+                             src->num_blocks * src->block_bytes;
+    const int64_t d_extent = (dst->num_planes > 1 ? (dst->num_planes - 1) * dst->plane_stride_bytes : 0) +
+                             dst->num_blocks * dst->block_bytes;
+    if (sb < db + d_extent && db < sb + s_extent) {
+        if (sb != db) return KVC_ERR_OVERLAP;  // partially overlapping pools: no safe reading
+        std::sort(srcs.begin(), srcs.end());
+        for (int64_t s : srcs)
+            if (std::binary_search(dsts.begin(), dsts.end(), s)) return KVC_ERR_OVERLAP;
+    }
+    return KVC_OK;
+}
+
+}  // extern "C"

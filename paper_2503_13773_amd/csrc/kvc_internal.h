@@ -1,0 +1,57 @@
+// Internal declarations shared by the HIP translation units of libkvc_hip.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvc.h"
+
+namespace kvc {
+
+// Everything the attention kernels need besides the tensor pointers.
+struct AttnParams {
+    int num_seqs;
+    int num_q_heads;
+    int num_kv_heads;
+    int group;              // num_q_heads / num_kv_heads
+    int block_size;
+    int block_size_log2;
+    int max_blocks_per_seq;
+    int partition_tokens;   // split-K partition length, multiple of 16
+    int max_partitions;     // partitions per sequence the grid and workspace provide for
+    int k_via_lds;          // MFMA kernel: stage K tiles through LDS (1) or load them in operand layout (0)
+    float scale;            // as given by the caller
+    float scale_log2e;      // scale * log2(e), for the base-2 softmax of the MFMA kernel
+};
+
+// Workspace layout: acc [num_seqs][num_q_heads][max_partitions][head_dim] fp32, then
+// ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum) at a
+// 256-byte aligned offset.
+struct Workspace {
+    float *acc;
+    float *ml;
+};
+
+constexpr int kThreads = 256;       // 4 wavefronts per workgroup, every attention kernel
+constexpr int kWaves = kThreads / 64;
+
+// Launchers (defined next to their kernels).  All enqueue on `stream` and return the
+// hipError_t of the launch.
+hipError_t launch_partial_valu(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens, void *out,
+                               Workspace ws, const AttnParams &p, int dtype, int head_dim,
+                               int grid, hipStream_t stream);
+hipError_t launch_partial_mfma(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens, void *out,
+                               Workspace ws, const AttnParams &p, int grid, hipStream_t stream);
+hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
+                        int dtype, int head_dim, bool base2, int grid, hipStream_t stream);
+hipError_t launch_block_copy(const kvc_pool &src, const kvc_pool &dst, const int64_t *mapping,
+                             int64_t num_pairs, hipStream_t stream);
+
+// Largest head chunk (8, 4, 2 or 1) the VALU kernel processes per workgroup for a group size.
+inline int valu_head_chunk(int group) {
+    return group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+}
+
+}  // namespace kvc

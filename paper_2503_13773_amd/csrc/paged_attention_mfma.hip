@@ -1,0 +1,312 @@
+// Split-K partial kernel of paged decode attention on the matrix cores (gfx950, bf16,
+// head_dim 128, block_size a multiple of 16, up to 16 query heads per KV head).
+//
+// One workgroup = one (sequence, KV head, partition of the context); all query heads that
+// share the KV head ride along as the 16 columns of an MFMA tile, so K and V are read from
+// HBM exactly once per KV head (grouped-query heads form a real dense tile: 16 tokens x
+// 128 dims x G heads).  The four wavefronts take 16-token tiles round-robin, each with its
+// own online softmax; they are merged through LDS at the end.
+//
+// Per 16-token tile and wavefront (lane = 16*quad + r):
+//   S[token][head]   = K[16 x 128] . Q^T[128 x 16]      4 x v_mfma_f32_16x16x32_bf16
+//       A operand: lane holds K[token r][32j + 8*quad .. +7]; B operand: the same dims of
+//       Q[head r].  K reaches that layout either straight from HBM (16 rows x 64 bytes per
+//       load instruction) or, in the LDS-staged variant, by fully coalesced 1 KiB loads, a
+//       16-byte XOR-swizzled write to LDS and a conflict-free 16-byte read back.
+//   softmax over the C layout: lane holds S[token 4*quad + i][head r], i < 4; the max over
+//       tokens is 3 in-lane max + 2 cross-quad shuffles.  exp2 with scale*log2(e) folded in.
+//   O^T[dim][head]  += V^T[128 x 16] . P^T[16 x 16]      8 x v_mfma_f32_16x16x16_bf16
+//       B operand P^T is exactly the C layout of S (tokens 4*quad + i, head r): no data
+//       movement.  A operand needs 4 tokens of one dim per lane; V is loaded row-wise (lane
+//       reads 16 bytes = dims 8r..8r+7 of tokens 4*quad + i: full 256-byte rows per 16
+//       lanes, coalesced) and the 4x8 patch is transposed in registers with 16 v_perm_b32.
+//       MFMA e then yields dims {8*row + e}: lane ends up with O[head r][32*quad .. +31].
+//   Every quantity attached to a head (max, sum, rescale factor, accumulator) lives in the
+//   lanes with that r, so the online-softmax rescale needs no cross-lane traffic.
+//
+// Softmax weights are rounded to bf16 for the P.V product and the normaliser sums the
+// *rounded* weights, so weights still sum to one.  Rows past the context in the last tile
+// get score -inf and their V data is zeroed (NaN there cannot leak).
+#include <math.h>
+
+#include "kvc_internal.h"
+
+namespace kvc {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128;
+constexpr int kTileTokens = 16;
+constexpr int kTileElems = kTileTokens * D;  // 2048 bf16 = 4 KiB
+
+__device__ inline uint16_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return uint16_t(u >> 16);
+}
+
+// two fp32 -> packed bf16 pair (round to nearest even), low half = a
+__device__ inline uint32_t pack_bf16(float a, float b) {
+    const floatx2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+template <int GP, bool KLDS>
+__global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
+    const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
+    const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
+    AttnParams p, int tiles_per_block_log2) {
+    // LDS: per-wavefront K staging (4 KiB each, KLDS only), reused after a barrier for the
+    // cross-wavefront merge: acc [4][GP][128] fp32, then m [4][16], l [4][16].
+    constexpr int kAccFloats = kWaves * GP * D;
+    constexpr int kMergeBytes = (kAccFloats + 2 * kWaves * 16) * 4;
+    constexpr int kStageBytes = KLDS ? kWaves * kTileElems * 2 : 0;
+    constexpr int kSmemBytes = kMergeBytes > kStageBytes ? kMergeBytes : kStageBytes;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+
+    // blockIdx.x = kv_head + num_kv_heads * (seq + num_seqs * partition).  Workgroups go
+    // round-robin over the 8 XCDs, so with 8 KV heads every XCD's L2 serves one KV head:
+    // blocks shared between sequences (a common prefix) are fetched into one L2 only.
+    const int item = blockIdx.x;
+    const int kvh = item % p.num_kv_heads;
+    const int seq = (item / p.num_kv_heads) % p.num_seqs;
+    const int part = item / (p.num_kv_heads * p.num_seqs);
+    const int G = p.group;
+    const int head0 = kvh * G;
+    const int ctx = context_lens[seq];
+    const int tid = threadIdx.x;
+
+    if (ctx <= 0) {  // empty context: zeros, written by partition 0
+        if (part == 0)
+            for (int i = tid; i < G * D; i += kThreads)
+                out[(size_t(seq) * p.num_q_heads + head0) * D + i] = 0;
+        return;
+    }
+    const int tok0 = part * p.partition_tokens;
+    if (tok0 >= ctx) return;
+    const int tok1 = min(ctx, tok0 + p.partition_tokens);
+
+    const int wave = tid >> 6, lane = tid & 63;
+    const int quad = lane >> 4, r = lane & 15;
+
+    const int ntile = (tok1 - tok0 + kTileTokens - 1) >> 4;
+    const int tile0 = tok0 >> 4;
+    const int my_n = wave < ntile ? (ntile - wave + kWaves - 1) / kWaves : 0;  // <= 64
+
+    // physical block of my i-th tile sits in lane i
+    const int32_t *table = block_tables + size_t(seq) * p.max_blocks_per_seq;
+    int my_blk = 0;
+    if (lane < my_n) my_blk = table[(tile0 + wave + kWaves * lane) >> tiles_per_block_log2];
+
+    // Q as the B operand of S = K.Q^T: lane (quad, r) holds Q[head r][32j + 8*quad .. +7]
+    bf16x8 qb[4];
+    {
+        const uint4 zero = {0u, 0u, 0u, 0u};
+        const uint16_t *qrow = q + (size_t(seq) * p.num_q_heads + head0 + r) * D + 8 * quad;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint4 w = zero;
+            if (r < G) w = *reinterpret_cast<const uint4 *>(qrow + 32 * j);
+            qb[j] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    floatx4 acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    const size_t head_elems = size_t(p.block_size) * D;
+    const size_t block_elems = head_elems * p.num_kv_heads;
+    const int sub_mask = (1 << tiles_per_block_log2) - 1;
+    unsigned char *stage = smem + wave * (kTileElems * 2);
+
+    auto issue = [&](uint4(&kr)[4], uint4(&vr)[4], int it) __attribute__((always_inline)) {
+        const int blk = __builtin_amdgcn_readlane(my_blk, it);
+        const int gt = tile0 + wave + kWaves * it;
+        const size_t base = size_t(blk) * block_elems + kvh * head_elems + size_t(gt & sub_mask) * kTileElems;
+        const uint16_t *kp = k_cache + base;
+        const uint16_t *vp = v_cache + base;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (KLDS) kr[i] = *reinterpret_cast<const uint4 *>(kp + i * 512 + lane * 8);
+            else      kr[i] = *reinterpret_cast<const uint4 *>(kp + r * D + 32 * i + 8 * quad);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            vr[i] = *reinterpret_cast<const uint4 *>(vp + (4 * quad + i) * D + 8 * r);
+    };
+
+    auto compute = [&](uint4(&kr)[4], uint4(&vr)[4], int it) __attribute__((always_inline)) {
+        const int gt = tile0 + wave + kWaves * it;
+        bf16x8 ka[4];
+        if (KLDS) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {  // loaded: token 4i + quad, 16-byte chunk r
+                const int t = 4 * i + quad;
+                *reinterpret_cast<uint4 *>(stage + t * 256 + ((r ^ t) & 15) * 16) = kr[i];
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {  // wanted: token r, chunk 4j + quad
+                const int c = 4 * j + quad;
+                ka[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(stage + r * 256 + ((c ^ r) & 15) * 16));
+            }
+            __builtin_amdgcn_wave_barrier();
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
+        }
+
+        floatx4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j], qb[j], s, 0, 0, 0);
+
+        const int trow = gt * kTileTokens + 4 * quad;  // token of s[0]
+        float sv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[i] = s[i] * p.scale_log2e;
+        if ((gt + 1) * kTileTokens > tok1) {  // ragged last tile (wavefront-uniform)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (trow + i >= tok1) {
+                    sv[i] = -INFINITY;
+                    vr[i] = uint4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+        float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m, mx);  // finite: every tile has at least one valid token
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        float pf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pf[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
+        const uint32_t p01 = pack_bf16(pf[0], pf[1]);
+        const uint32_t p23 = pack_bf16(pf[2], pf[3]);
+        const float psum = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
+                           (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
+        l = fmaf(l, alpha, psum);
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+        }
+        const uint2 pw = {p01, p23};
+        const shortx4 pb = __builtin_bit_cast(shortx4, pw);
+
+        const uint32_t v0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
+        const uint32_t v1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
+        const uint32_t v2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
+        const uint32_t v3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            // dword w of a row holds dims 8r+2w (low half) and 8r+2w+1 (high half)
+            const uint2 lo = {__builtin_amdgcn_perm(v1[w], v0[w], 0x05040100u),
+                              __builtin_amdgcn_perm(v3[w], v2[w], 0x05040100u)};
+            const uint2 hi = {__builtin_amdgcn_perm(v1[w], v0[w], 0x07060302u),
+                              __builtin_amdgcn_perm(v3[w], v2[w], 0x07060302u)};
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, lo), pb, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, hi), pb, acc[2 * w + 1], 0, 0, 0);
+        }
+    };
+
+    uint4 kA[4], vA[4], kB[4], vB[4];
+    if (my_n > 0) issue(kA, vA, 0);
+    for (int it = 0; it < my_n; it += 2) {
+        const bool has1 = it + 1 < my_n;
+        if (has1) issue(kB, vB, it + 1);
+        compute(kA, vA, it);
+        if (has1) {
+            if (it + 2 < my_n) issue(kA, vA, it + 2);
+            compute(kB, vB, it + 1);
+        }
+    }
+
+    // per-head sum over the 4 quads (the max is already common to them)
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    float *sm_acc = reinterpret_cast<float *>(smem);  // [kWaves][GP][D]
+    float *sm_m = sm_acc + kAccFloats;                // [kWaves][16]
+    float *sm_l = sm_m + kWaves * 16;                 // [kWaves][16]
+    if (KLDS) __syncthreads();  // staging areas are about to be overwritten
+    if (r < G) {
+        float *dst = sm_acc + (size_t(wave) * GP + r) * D + 32 * quad;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<float4 *>(dst + 8 * i) = float4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+            *reinterpret_cast<float4 *>(dst + 8 * i + 4) = float4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+        }
+        if (quad == 0) {
+            sm_m[wave * 16 + r] = m;
+            sm_l[wave * 16 + r] = l;
+        }
+    }
+    __syncthreads();
+
+    const bool single = ctx <= p.partition_tokens;
+    for (int i = tid; i < G * D; i += kThreads) {
+        const int g = i >> 7, d = i & (D - 1);
+        float M = sm_m[g];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w * 16 + g]);
+        float L = 0.f, A = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + g] - M);  // idle wavefront: exp2(-inf) = 0
+            L = fmaf(wgt, sm_l[w * 16 + g], L);
+            A = fmaf(wgt, sm_acc[(size_t(w) * GP + g) * D + d], A);
+        }
+        const size_t row = size_t(seq) * p.num_q_heads + head0 + g;
+        if (single) {
+            out[row * D + d] = f32_to_bf16_rne(A / L);
+        } else {
+            const size_t slot = row * p.max_partitions + part;
+            ws.acc[slot * D + d] = A;
+            if (d == 0) {
+                ws.ml[slot * 2] = M;
+                ws.ml[slot * 2 + 1] = L;
+            }
+        }
+    }
+}
+
+template <int GP>
+void launch_gp(bool klds, const void *q, const void *k, const void *v, const int32_t *bt,
+               const int32_t *cl, void *out, Workspace ws, const AttnParams &p, int tpb_log2,
+               int grid, hipStream_t stream) {
+    const auto *qq = static_cast<const uint16_t *>(q);
+    const auto *kk = static_cast<const uint16_t *>(k);
+    const auto *vv = static_cast<const uint16_t *>(v);
+    auto *oo = static_cast<uint16_t *>(out);
+    if (klds)
+        pa_partial_mfma_kernel<GP, true><<<dim3(grid), dim3(kThreads), 0, stream>>>(qq, kk, vv, bt, cl, oo, ws, p, tpb_log2);
+    else
+        pa_partial_mfma_kernel<GP, false><<<dim3(grid), dim3(kThreads), 0, stream>>>(qq, kk, vv, bt, cl, oo, ws, p, tpb_log2);
+}
+
+}  // namespace
+
+hipError_t launch_partial_mfma(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens, void *out,
+                               Workspace ws, const AttnParams &p, int grid, hipStream_t stream) {
+    int tpb_log2 = 0;
+    while ((16 << tpb_log2) < p.block_size) ++tpb_log2;
+    const bool klds = p.k_via_lds != 0;
+    if (p.group <= 4) launch_gp<4>(klds, q, k_cache, v_cache, block_tables, context_lens, out, ws, p, tpb_log2, grid, stream);
+    else if (p.group <= 8) launch_gp<8>(klds, q, k_cache, v_cache, block_tables, context_lens, out, ws, p, tpb_log2, grid, stream);
+    else launch_gp<16>(klds, q, k_cache, v_cache, block_tables, context_lens, out, ws, p, tpb_log2, grid, stream);
+    return hipGetLastError();
+}
+
+}  // namespace kvc

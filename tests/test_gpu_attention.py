@@ -1,0 +1,270 @@
+"""Parity of the HIP paged decode attention with the fp64 oracle (needs an MI355X).
+
+Every case calls the kernels through the C ABI (ctypes binding) on seeded inputs and
+compares with oracle.paged_attention_decode element by element: max-abs error <= 2e-2
+for bf16 tensors and <= 1e-5 for fp32 tensors.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvc_workloads as W
+from gpu_util import BF16_TOL, F32_TOL, dev_tensor, out_bits, out_to_f64, run_gpu, to_device, tol_of
+
+pytestmark = pytest.mark.gpu
+
+VALU, MFMA, MFMA_LDS = 1, 2, 3
+
+
+def check(w, oracle_mod, label, **opts):
+    print(f"[case] {label} {w.name} nseq={w.num_seqs} opts={opts}", flush=True)
+    got = out_to_f64(run_gpu(w, **opts))
+    ref = oracle_mod.attention_of_workload(w, num_threads=8)
+    err = np.abs(got - ref).max()
+    assert np.isfinite(got).all()
+    assert err <= tol_of(w), (label, err)
+    return err
+
+
+def custom(seed, *, dtype, lens, hq, hkv, d, bs, nb_extra=7, lmax=None, name="custom"):
+    rng = np.random.default_rng(seed)
+    lens = np.asarray(lens, dtype=np.int32)
+    nblk = W.blocks_needed(lens, bs)
+    lmax = lmax or int(max(1, nblk.max())) + 2
+    return W.build_workload(name, rng, dtype=dtype, context_lens=lens, num_q_heads=hq,
+                            num_kv_heads=hkv, head_dim=d, block_size=bs, max_blocks_per_seq=lmax,
+                            num_pool_blocks=int(nblk.sum()) + nb_extra)
+
+
+# ---------------------------------------------------------------------------
+# the named configurations at oracle-sized scale, every element compared
+# ---------------------------------------------------------------------------
+def test_cfg1_tiny_fp32(oracle_mod):
+    w = W.make_config("cfg1")
+    check(w, oracle_mod, "cfg1")
+    check(w, oracle_mod, "cfg1 split", partition_tokens=64)
+    check(w, oracle_mod, "cfg1 loose bound", tight=False)
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("name,nseq,scale", [("cfg2", 6, 0.5), ("cfg3", 12, 0.5), ("cfg4", 2, 0.04),
+                                             ("cfg5", 16, 0.5)])
+def test_configs_small_every_element(oracle_mod, name, nseq, scale, kernel):
+    w = W.make_config(name, num_seqs=nseq, ctx_scale=scale)
+    check(w, oracle_mod, f"{name} small", kernel=kernel)
+    check(w, oracle_mod, f"{name} small pt=64", kernel=kernel, partition_tokens=64)
+
+
+# ---------------------------------------------------------------------------
+# the named configurations at full size, in the launch configuration the bench times:
+# sampled (sequence, head) rows against the oracle
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg3b", "cfg4", "cfg5"])
+def test_configs_full_size_sampled_rows(oracle_mod, name):
+    w = W.make_config(name)
+    print(f"[case] full {name} mean ctx {w.context_lens.mean():.0f}", flush=True)
+    got = out_to_f64(run_gpu(w))
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(7)
+    order = np.argsort(w.context_lens)
+    seqs = set(int(s) for s in order[:2]) | set(int(s) for s in order[-2:])
+    seqs |= set(int(s) for s in rng.integers(0, w.num_seqs, 6))
+    rows = [(s, int(h)) for s in sorted(seqs) for h in rng.choice(w.num_q_heads, 4, replace=False)]
+    ref = oracle_mod.attention_of_workload(w, rows=rows, num_threads=8)
+    err = max(np.abs(got[s, h] - ref[s, h]).max() for s, h in rows)
+    assert err <= BF16_TOL, (name, err)
+    # property that holds at any size: each output is a convex combination of V rows
+    vmax = float(W.bf16_bits_to_f32(w.v_cache.reshape(-1)[:1 << 22]).__abs__().max())
+    assert np.abs(got).max() <= max(vmax, 6.0) * 1.01
+
+
+# ---------------------------------------------------------------------------
+# shapes, tails and degenerate cases
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+def test_ragged_tails_and_partition_edges(oracle_mod, kernel):
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513]
+    w = custom(101, dtype=W.BF16, lens=lens, hq=8, hkv=2, d=128, bs=16)
+    for pt in (0, 16, 64, 128, 256):
+        check(w, oracle_mod, f"tails pt={pt}", kernel=kernel, partition_tokens=pt)
+
+
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (2, 1), (3, 1), (4, 1), (8, 1), (16, 1), (12, 4), (5, 5), (40, 8)])
+def test_group_sizes(oracle_mod, hq, hkv):
+    w = custom(102, dtype=W.BF16, lens=[40, 200, 77], hq=hq, hkv=hkv, d=128, bs=16)
+    for kernel in (VALU, MFMA, MFMA_LDS):
+        check(w, oracle_mod, f"group {hq}/{hkv}", kernel=kernel, partition_tokens=64)
+
+
+def test_group_larger_than_16_takes_valu(oracle_mod):
+    import paper_2503_13773_amd as K
+    w = custom(103, dtype=W.BF16, lens=[50, 90], hq=32, hkv=1, d=128, bs=16)
+    d = to_device(w)
+    desc = K.attn_desc(d["q"], d["k"], d["tables"])
+    assert K.attn_plan(desc).kernel == VALU
+    check(w, oracle_mod, "group 32")
+    with pytest.raises(K.KvcError):
+        run_gpu(w, kernel=MFMA)
+
+
+@pytest.mark.parametrize("bs", [1, 2, 4, 8, 16, 32, 64])
+def test_block_sizes(oracle_mod, bs):
+    w = custom(104, dtype=W.BF16, lens=[5, 70, 131], hq=8, hkv=2, d=128, bs=bs)
+    check(w, oracle_mod, f"bs={bs} valu", kernel=VALU, partition_tokens=64)
+    if bs >= 16:
+        check(w, oracle_mod, f"bs={bs} mfma", kernel=MFMA, partition_tokens=64)
+        check(w, oracle_mod, f"bs={bs} mfma lds", kernel=MFMA_LDS, partition_tokens=64)
+    wf = custom(105, dtype=W.F32, lens=[5, 70, 131], hq=4, hkv=2, d=64, bs=bs)
+    check(wf, oracle_mod, f"bs={bs} f32", partition_tokens=32)
+
+
+@pytest.mark.parametrize("dtype,d", [(W.F32, 64), (W.F32, 128), (W.BF16, 64), (W.BF16, 128)])
+def test_dtype_head_dim_grid(oracle_mod, dtype, d):
+    w = custom(106, dtype=dtype, lens=[33, 260, 9, 100], hq=8, hkv=4, d=d, bs=16)
+    check(w, oracle_mod, f"{dtype} d={d}")
+    check(w, oracle_mod, f"{dtype} d={d} pt=48", partition_tokens=48)
+
+
+def test_fp32_long_context_stays_within_1e5(oracle_mod):
+    w = custom(107, dtype=W.F32, lens=[4096, 3000], hq=2, hkv=2, d=64, bs=16)
+    assert check(w, oracle_mod, "f32 long") <= F32_TOL
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+def test_maximum_partition_length(oracle_mod, kernel):
+    w = custom(108, dtype=W.BF16, lens=[4096, 4095, 8200], hq=4, hkv=1, d=128, bs=16)
+    check(w, oracle_mod, "pt=4096", kernel=kernel, partition_tokens=4096)
+
+
+@pytest.mark.parametrize("dtype,kernels", [(W.F32, [VALU]), (W.BF16, [VALU, MFMA, MFMA_LDS])])
+def test_context_one_returns_v_bit_exactly(dtype, kernels):
+    d_ = 64 if dtype == W.F32 else 128
+    w = custom(109, dtype=dtype, lens=[1, 1, 1, 1], hq=8, hkv=2, d=d_, bs=16)
+    for kernel in kernels:
+        for pt in (0, 16):   # pt=16 with the loose bound goes through empty partitions
+            out = run_gpu(w, kernel=kernel, partition_tokens=pt, tight=(pt == 0))
+            bits = out_bits(out)
+            for n in range(4):
+                blk = w.block_tables[n, 0]
+                for h in range(8):
+                    want = w.v_cache[blk, h // 4, 0, :]
+                    want = want.view(np.int16) if dtype == W.BF16 else want.view(np.int32)
+                    assert np.array_equal(bits[n, h], want), (kernel, pt, n, h)
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_context_zero_gives_zeros_and_leaves_neighbours_alone(oracle_mod, dtype):
+    d_ = 64 if dtype == W.F32 else 128
+    w = custom(110, dtype=dtype, lens=[0, 37, 0, 300, 0], hq=4, hkv=2, d=d_, bs=16)
+    w.block_tables[[0, 2, 4], :] = -1
+    kernels = [VALU] if dtype == W.F32 else [VALU, MFMA, MFMA_LDS]
+    ref = oracle_mod.attention_of_workload(w)
+    for kernel in kernels:
+        for pt in (0, 64):
+            dv = to_device(w)
+            import paper_2503_13773_amd as K
+            out = torch.full_like(dv["q"], 7.0)
+            K.paged_attention_decode(dv["q"], dv["k"], dv["v"], dv["tables"], dv["lens"], w.scale,
+                                     out, kernel=kernel, partition_tokens=pt, max_context_len=300)
+            got = out_to_f64(out)
+            assert np.array_equal(got[[0, 2, 4]], np.zeros_like(got[[0, 2, 4]]))
+            assert np.abs(got - ref).max() <= tol_of(w)
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+def test_poison_beyond_context_and_in_unused_entries(oracle_mod, kernel):
+    """NaN in slots past the context, in unused blocks; -1 / huge ids in unused table entries."""
+    w = custom(111, dtype=W.BF16, lens=[5, 16, 17, 100, 250, 1], hq=8, hkv=2, d=128, bs=16, nb_extra=9)
+    clean = out_bits(run_gpu(w, kernel=kernel, partition_tokens=64))
+    nan = np.uint16(0x7FC0)
+    used = np.zeros(w.num_pool_blocks, dtype=bool)
+    nblk = W.blocks_needed(w.context_lens, 16)
+    for n, L in enumerate(w.context_lens):
+        used[w.block_tables[n, :nblk[n]]] = True
+        if L % 16:
+            b = w.block_tables[n, nblk[n] - 1]
+            w.k_cache[b, :, L % 16:, :] = nan
+            w.v_cache[b, :, L % 16:, :] = nan
+        w.block_tables[n, nblk[n]:] = 2 ** 30 if n % 2 else -1
+    w.k_cache[~used] = nan
+    w.v_cache[~used] = nan
+    dirty = out_bits(run_gpu(w, kernel=kernel, partition_tokens=64))
+    assert np.array_equal(clean, dirty)
+    check(w, oracle_mod, "poisoned", kernel=kernel, partition_tokens=64)
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+def test_placement_invariance_is_bitwise_on_gpu(kernel):
+    """Same logical KV at another physical placement / pool size: identical output bits."""
+    w = custom(112, dtype=W.BF16, lens=[70, 300, 33], hq=8, hkv=2, d=128, bs=16)
+    a = out_bits(run_gpu(w, kernel=kernel, partition_tokens=128))
+    rng = np.random.default_rng(5)
+    nb2 = w.num_pool_blocks + 11
+    perm = rng.permutation(nb2)[:w.num_pool_blocks]
+    k2 = np.zeros((nb2,) + w.k_cache.shape[1:], dtype=np.uint16)
+    v2 = np.zeros_like(k2)
+    k2[perm] = w.k_cache
+    v2[perm] = w.v_cache
+    t2 = w.block_tables.copy()
+    t2[t2 >= 0] = perm[t2[t2 >= 0]]
+    w.k_cache, w.v_cache, w.block_tables, w.num_pool_blocks = k2, v2, t2, nb2
+    b = out_bits(run_gpu(w, kernel=kernel, partition_tokens=128))
+    assert np.array_equal(a, b)
+
+
+def test_shared_prefix_equals_private_copies(oracle_mod):
+    """Block ids referenced by several tables give what private copies of the same data give."""
+    w = W.make_config("cfg5", num_seqs=24, ctx_scale=0.4)
+    assert w.extra["share_groups"]
+    shared = out_bits(run_gpu(w))
+    nblk = W.blocks_needed(w.context_lens, 16)
+    total = int(nblk.sum())
+    k2 = np.zeros((total,) + w.k_cache.shape[1:], dtype=np.uint16)
+    v2 = np.zeros_like(k2)
+    t2 = np.full_like(w.block_tables, -1)
+    pos = 0
+    for n in range(w.num_seqs):
+        ids = w.block_tables[n, :nblk[n]]
+        k2[pos:pos + nblk[n]] = w.k_cache[ids]
+        v2[pos:pos + nblk[n]] = w.v_cache[ids]
+        t2[n, :nblk[n]] = np.arange(pos, pos + nblk[n])
+        pos += nblk[n]
+    w.k_cache, w.v_cache, w.block_tables, w.num_pool_blocks = k2, v2, t2, total
+    private = out_bits(run_gpu(w))
+    assert np.array_equal(shared, private)
+
+
+def test_partial_then_merge_equals_the_fused_call():
+    import paper_2503_13773_amd as K
+    w = W.make_config("cfg3", num_seqs=8, ctx_scale=0.5)
+    d = to_device(w)
+    desc = K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=w.max_context_len)
+    ws = torch.empty(K.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    a = K.paged_attention_decode(d["q"], d["k"], d["v"], d["tables"], d["lens"], w.scale, desc=desc,
+                                 workspace=ws)
+    b = torch.zeros_like(d["q"])
+    K.paged_attention_decode_partial(d["q"], d["k"], d["v"], d["tables"], d["lens"], w.scale, b, desc, ws)
+    K.paged_attention_decode_merge(d["lens"], b, desc, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out_bits(a), out_bits(b))
+
+
+def test_runs_on_a_side_stream_and_validates_inputs():
+    import paper_2503_13773_amd as K
+    w = W.make_config("cfg3", num_seqs=4, ctx_scale=0.3)
+    d = to_device(w)
+    ref = out_bits(run_gpu(w, d))
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = K.paged_attention_decode(d["q"], d["k"], d["v"], d["tables"], d["lens"], w.scale,
+                                       max_context_len=w.max_context_len)
+    s.synchronize()
+    assert np.array_equal(out_bits(out), ref)
+    desc = K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=w.max_context_len)
+    assert K.validate_attention_inputs(d["tables"], d["lens"], desc) == 0
+    bad = d["tables"].clone()
+    bad[1, 0] = w.num_pool_blocks
+    assert K.validate_attention_inputs(bad, d["lens"], desc) == -8
+    long = d["lens"].clone()
+    long[0] = w.max_context_len + 1
+    assert K.validate_attention_inputs(d["tables"], long, desc) == -8
