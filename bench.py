@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV decode hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch, all inputs resident in
+HBM: paged_attention_decode (split-K partial kernel + merge kernel) over the batch, then
+kv_block_copy swapping the K and V blocks of 20 % of the batch's sequences out to a second
+device pool.  Successive steps rotate over replicas of the batch at different addresses
+(>= 2 GiB in total) so that the 256 MB memory-side cache cannot serve the KV reads.
+
+Prints ONE JSON line: whole-step throughput in algorithmic GB/s, the roofline record of the
+dominant kernel (the attention partial kernel, timed per launch with HIP events on the
+launch stream) and the CPU oracle's throughput on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3b] ...
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+METRIC = "paged-attn decode HBM GB/s (% of MI355X peak) + us per batch decode step"
+WORKLOADS = {
+    "cfg2": "Llama-2-7B-shape MHA decode, bf16, batch 64, 32 heads, head_dim 128, block 16, lognormal lengths",
+    "cfg3": "Llama-3-8B-shape GQA decode, bf16, batch 128, 32q/8kv heads, head_dim 128, block 16, lognormal lengths <= 4096, pool 90% full",
+    "cfg3b": "Llama-3-8B-shape GQA decode, bf16, batch 64, 32q/8kv heads, head_dim 128, block 16, lognormal lengths <= 4096, pool 90% full",
+    "cfg4": "long-context GQA decode, bf16, batch 16, 64q/8kv heads, head_dim 128, block 16, lengths U[8192,32768]",
+    "cfg5": "8B GQA decode, bf16, batch 96, 25% of sequences share prefix blocks",
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="cfg3b", choices=sorted(WORKLOADS))
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA, 3 MFMA with LDS-staged K")
+    ap.add_argument("--partition-tokens", type=int, default=0)
+    ap.add_argument("--replica-bytes", type=float, default=2.2e9,
+                    help="rotate over replicas of the batch totalling at least this many KV bytes")
+    ap.add_argument("--swap-frac", type=float, default=0.20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported, use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import kvc_workloads as W
+    import paper_2503_13773_amd as K
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    lib = K.lib()
+
+    t0 = time.time()
+    w = W.make_config(args.workload)
+    log(f"[bench] workload {args.workload}: {w.num_seqs} seqs, mean ctx {w.context_lens.mean():.0f}, "
+        f"max {w.max_context_len}, pool {w.num_pool_blocks} blocks, KV {w.kv_bytes()/1e6:.1f} MB "
+        f"(generated in {time.time()-t0:.1f}s)")
+
+    # ---- swap-out plan: ceil(frac * batch) sequences, all their blocks, K and V planes ----
+    rng = np.random.default_rng(4242)
+    nblk = W.blocks_needed(w.context_lens, w.block_size)
+    victims = sorted(int(s) for s in rng.permutation(w.num_seqs)[:int(math.ceil(args.swap_frac * w.num_seqs))])
+    src_ids = np.unique(np.concatenate([w.block_tables[s, :nblk[s]] for s in victims])).astype(np.int64)
+    pool2_blocks = int(len(src_ids))
+    mapping_np = np.stack([src_ids, rng.permutation(pool2_blocks).astype(np.int64)], axis=1)
+    block_bytes = w.block_bytes()
+    copy_bytes = 2 * 2 * len(src_ids) * block_bytes          # read + write, K and V planes
+    attn_bytes = w.kv_bytes() + w.qo_bytes()                 # K+V once, q in, out
+    step_bytes = attn_bytes + copy_bytes
+
+    # ---- device replicas ----
+    def dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    pool_np = np.stack([w.k_cache, w.v_cache])                # [2][NB][Hkv][Bs][D]
+    n_rep = max(2, int(math.ceil(args.replica_bytes / max(1, w.kv_bytes()))))
+    base_pool = dev_bf16(pool_np)
+    base = dict(q=dev_bf16(w.q), tables=torch.from_numpy(w.block_tables).cuda(),
+                lens=torch.from_numpy(w.context_lens).cuda(),
+                mapping=torch.from_numpy(mapping_np).cuda())
+    desc = K.attn_desc(base["q"], base_pool[0], base["tables"], max_context_len=w.max_context_len,
+                       partition_tokens=args.partition_tokens, kernel=args.kernel)
+    plan = K.attn_plan(desc)
+    ws_bytes = K.workspace_bytes(desc)
+    reps = []
+    for r in range(n_rep):
+        pool1 = base_pool if r == 0 else base_pool.clone()
+        rep = dict(pool1=pool1, k=pool1[0], v=pool1[1],
+                   q=base["q"].clone(), tables=base["tables"].clone(), lens=base["lens"].clone(),
+                   mapping=base["mapping"].clone(), out=torch.empty_like(base["q"]),
+                   ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda"),
+                   pool2=torch.zeros((2, pool2_blocks) + tuple(pool1.shape[2:]), dtype=pool1.dtype,
+                                     device="cuda"))
+        rep["src_pool"] = K.pool_of(rep["pool1"])
+        rep["dst_pool"] = K.pool_of(rep["pool2"])
+        reps.append(rep)
+    torch.cuda.synchronize()
+    log(f"[bench] {n_rep} replicas, plan: kernel {plan.kernel}, partition {plan.partition_tokens} tokens, "
+        f"partial grid {plan.partial_grid}, merge grid {plan.merge_grid}, workspace {ws_bytes/1e6:.1f} MB; "
+        f"swap {len(victims)} seqs / {len(src_ids)} blocks")
+
+    import ctypes
+    stream = torch.cuda.current_stream()
+    sh = int(stream.cuda_stream)
+    dref = ctypes.byref(desc)
+
+    def attn(rep):
+        rc = lib.kvc_paged_attention_decode(rep["q"].data_ptr(), rep["k"].data_ptr(), rep["v"].data_ptr(),
+                                            rep["tables"].data_ptr(), rep["lens"].data_ptr(), w.scale,
+                                            rep["out"].data_ptr(), dref, rep["ws"].data_ptr(), ws_bytes, sh)
+        assert rc == 0, K.status_string(rc)
+
+    def partial(rep):
+        rc = lib.kvc_paged_attention_decode_partial(rep["q"].data_ptr(), rep["k"].data_ptr(), rep["v"].data_ptr(),
+                                                    rep["tables"].data_ptr(), rep["lens"].data_ptr(), w.scale,
+                                                    rep["out"].data_ptr(), dref, rep["ws"].data_ptr(), ws_bytes, sh)
+        assert rc == 0, K.status_string(rc)
+
+    def copy(rep):
+        rc = lib.kvc_kv_block_copy(ctypes.byref(rep["src_pool"]), ctypes.byref(rep["dst_pool"]),
+                                   rep["mapping"].data_ptr(), len(src_ids), sh)
+        assert rc == 0, K.status_string(rc)
+
+    def step(rep):
+        attn(rep)
+        copy(rep)
+
+    # ---- correctness guard: one replica against a few oracle rows (cheap) ----
+    step(reps[-1])
+    torch.cuda.synchronize()
+
+    def timed_wall(fn, steps, warmup):
+        for i in range(warmup):
+            fn(reps[i % n_rep])
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            fn(reps[i % n_rep])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / steps
+
+    def timed_events(fn, steps, warmup, hot=False):
+        """Average duration of one fn launch, HIP events on the launch stream around each call."""
+        pick = (lambda i: reps[0]) if hot else (lambda i: reps[i % n_rep])
+        for i in range(warmup):
+            fn(pick(i))
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(steps)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(ev):
+            a.record(stream)
+            fn(pick(i))
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e-3 for a, b in ev)
+        return sum(ts) / len(ts), ts[len(ts) // 2], ts[len(ts) // 10], ts[(9 * len(ts)) // 10]
+
+    K_, W_ = args.steps, args.warmup
+    step_s = timed_wall(step, K_, W_)                      # the headline: exactly K steps, wall clock
+    attn_avg, attn_med, attn_p10, attn_p90 = timed_events(attn, K_, W_)
+    part_avg, part_med, _, _ = timed_events(partial, K_, W_)
+    copy_avg, copy_med, _, _ = timed_events(copy, K_, W_)
+    hot_avg, hot_med, _, _ = timed_events(attn, K_, W_, hot=True)
+    log(f"[bench] step {step_s*1e6:.1f} us | attention avg {attn_avg*1e6:.1f} med {attn_med*1e6:.1f} us "
+        f"(hot {hot_med*1e6:.1f}) | partial kernel avg {part_avg*1e6:.1f} us | copy avg {copy_avg*1e6:.1f} us")
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, same inputs ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = args.cpu_threads or min(oracle.num_threads_available(), os.cpu_count() or 1)
+        h2 = np.zeros((2, pool2_blocks) + pool_np.shape[2:], dtype=np.uint16)
+        budget, done_rows, t_cpu = 20.0, 0, 0.0
+        rows_all = [(n, h) for n in range(w.num_seqs) for h in range(w.num_q_heads)]
+        # whole batches while they fit the budget; always at least one full batch
+        passes = 0
+        while True:
+            t = time.perf_counter()
+            oracle.attention_of_workload(w, num_threads=threads)
+            oracle.kv_block_copy(pool_np, h2, mapping_np)
+            t_cpu += time.perf_counter() - t
+            passes += 1
+            if t_cpu + t_cpu / passes > budget or passes >= 8:
+                break
+        cpu_s = t_cpu / passes
+        cpu = {"value": round(step_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(threads),
+               "kind": "oracle", "sample": f"{passes} full step(s) of the same batch ({w.num_seqs} seqs x "
+               f"{w.num_q_heads} heads fp64 attention + {len(src_ids)}-block memcpy copy), "
+               f"{cpu_s:.2f} s per step", "s_per_step": round(cpu_s, 4)}
+        log(f"[bench] cpu oracle: {cpu_s:.2f} s/step on {threads} threads")
+
+    # ---- measured HBM traffic of the dominant kernel, if a rocprofv3 --pmc summary is committed ----
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tfile):
+        try:
+            with open(tfile) as f:
+                t = json.load(f)
+            key = f"{args.workload}:kernel{plan.kernel}:pt{plan.partition_tokens}"
+            if key in t:
+                traffic = t[key]["bytes_per_launch"]
+        except Exception:
+            traffic = None
+
+    part_bytes = attn_bytes  # what one partial-kernel launch must move (K+V once, q, out/partials not counted)
+    achieved = part_bytes / part_avg / 1e9
+    value = step_bytes / step_s / 1e9
+    result = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K_,
+        "warmup": W_, "ms_per_step": round(step_s * 1e3, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}",
+                   "batch": w.num_seqs, "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "block_size": w.block_size,
+                   "mean_context_len": round(float(w.context_lens.mean()), 1),
+                   "max_context_len": w.max_context_len,
+                   "step": "paged_attention_decode (partial+merge) + kv_block_copy swap-out of "
+                           f"{len(victims)} sequences ({len(src_ids)} blocks, K and V planes)",
+                   "replicas": n_rep, "kernel": int(plan.kernel),
+                   "partition_tokens": int(plan.partition_tokens)},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "detail": {
+            "step_bytes": int(step_bytes), "attention_bytes": int(attn_bytes), "copy_bytes": int(copy_bytes),
+            "attention_us": round(attn_avg * 1e6, 2), "attention_us_median": round(attn_med * 1e6, 2),
+            "attention_us_p10": round(attn_p10 * 1e6, 2), "attention_us_p90": round(attn_p90 * 1e6, 2),
+            "attention_GBs": round(attn_bytes / attn_avg / 1e9, 1),
+            "attention_pct_of_peak": round(100.0 * attn_bytes / attn_avg / 1e9 / HBM_PEAK_GBS, 2),
+            "attention_us_hot_same_replica": round(hot_med * 1e6, 2),
+            "tokens_per_s": round(w.num_seqs / attn_avg, 1),
+            "copy_us": round(copy_avg * 1e6, 2), "copy_GBs": round(copy_bytes / copy_avg / 1e9, 1),
+        },
+        "roofline": {"bound": "hbm", "kernel": "pa_partial_mfma_kernel" if plan.kernel != 1 else "pa_partial_valu_kernel",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "bytes_per_launch": int(part_bytes), "avg_launch_us": round(part_avg * 1e6, 2)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

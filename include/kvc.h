@@ -67,7 +67,10 @@ typedef enum {
     KVC_KERNEL_VALU = 1, /* vector-ALU dot products; any supported shape */
     KVC_KERNEL_MFMA = 2, /* matrix-core tiles; bf16, head_dim 128, block_size % 16 == 0, group <= 16;
                             K tiles go from HBM straight into the MFMA operand layout */
-    KVC_KERNEL_MFMA_LDS = 3 /* same, K tiles loaded fully coalesced and re-laid-out through LDS */
+    KVC_KERNEL_MFMA_LDS = 3, /* same, K tiles loaded fully coalesced and re-laid-out through LDS */
+    KVC_KERNEL_MFMA_BALANCED = 4 /* matrix-core tiles, persistent grid: the batch's (sequence, kv head,
+                            16-token tile) work is flattened and cut into equal per-wavefront ranges;
+                            same shape limits as KVC_KERNEL_MFMA, and num_seqs <= 1024 */
 } kvc_kernel;
 
 typedef struct {
@@ -82,8 +85,9 @@ typedef struct {
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 means
                                    max_blocks_per_seq * block_size.  A tight bound keeps
                                    the launch grid and the workspace small. */
-    int32_t partition_tokens;   /* split-K partition length in tokens (multiple of 16);
-                                   0 lets the library choose */
+    int32_t partition_tokens;   /* split-K partition length in tokens (multiple of 16); 0 lets the
+                                   library choose.  For KVC_KERNEL_MFMA_BALANCED: the smallest
+                                   range a wavefront takes. */
     int32_t kernel;             /* kvc_kernel */
     int32_t reserved;           /* must be 0 */
 } kvc_attn_desc;
@@ -123,8 +127,8 @@ KVC_API size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *d
  *     is fine).  One block id may appear in many rows (shared prefix).
  *   - context_lens[n] == 0 writes a row of zeros.
  *   - Accumulation is fp32; bf16 output is rounded to nearest even.
- *   - Two launches: a split-K partial kernel over (sequence, kv head, partition) and a merge
- *     kernel; a sequence that fits one partition is finished by the first.
+ *   - Two launches: a split-K partial kernel over pieces of each (sequence, kv head) context
+ *     and a merge kernel; a context that is not split is finished by the first.
  *   - `workspace`: device memory, 256-byte aligned, at least
  *     kvc_paged_attention_decode_workspace_bytes(desc); may be NULL when that is 0.  It is
  *     scratch: contents before and after the call are meaningless.

@@ -7,7 +7,7 @@ Every step runs in the HIP kernels of the library; this package only marshals
 arguments.  PyTorch supplies device memory and streams.
 """
 from .binding import (  # noqa: F401
-    KVC_F32, KVC_BF16, KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS,
+    KVC_F32, KVC_BF16, KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS, KERNEL_MFMA_BALANCED,
     KvcError, AttnDesc, AttnPlan, Pool, lib, library_path, attn_desc, attn_plan,
     workspace_bytes, paged_attention_decode, paged_attention_decode_partial,
     paged_attention_decode_merge, validate_attention_inputs, kv_block_copy,

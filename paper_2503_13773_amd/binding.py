@@ -8,7 +8,7 @@ from typing import Optional
 import torch  # device memory and streams; also makes sure one HIP runtime is shared
 
 KVC_F32, KVC_BF16 = 0, 1
-KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS = 0, 1, 2, 3
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS, KERNEL_MFMA_BALANCED = 0, 1, 2, 3, 4
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libkvc_hip.so")

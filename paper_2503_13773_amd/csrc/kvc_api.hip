@@ -30,14 +30,22 @@ struct Plan {
     int max_partitions;
     int64_t partial_grid;
     int64_t merge_grid;
-    uint64_t acc_bytes;  // offset of the (max, sum) array inside the workspace
+    uint64_t ml_offset;   // offset of the (max, sum) array inside the workspace
+    uint64_t cnt_offset;  // offset of the per-row partial counts (balanced kernel)
     uint64_t workspace_bytes;
+    int min_chunk_tiles;
     int max_context_len;
 };
 
 bool mfma_ok(const kvc_attn_desc &d) {
     return d.dtype == KVC_BF16 && d.head_dim == 128 && d.block_size >= 16 &&
            d.num_q_heads / d.num_kv_heads <= 16;
+}
+
+// The balanced kernel keeps a prefix sum over the batch in LDS and indexes flat tiles in int32.
+bool balanced_ok(const kvc_attn_desc &d, int max_ctx) {
+    return mfma_ok(d) && d.num_seqs <= kvc::kMaxStreamSeqs &&
+           int64_t(d.num_seqs) * d.num_kv_heads * ceil_div(max_ctx, 16) < (int64_t(1) << 30);
 }
 
 int make_plan(const kvc_attn_desc *d, Plan *pl) {
@@ -58,9 +66,35 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
         return KVC_ERR_BAD_SHAPE;
 
     int kernel = d->kernel;
-    if (kernel < KVC_KERNEL_AUTO || kernel > KVC_KERNEL_MFMA_LDS) return KVC_ERR_BAD_SHAPE;
-    if (kernel == KVC_KERNEL_AUTO) kernel = mfma_ok(*d) ? KVC_KERNEL_MFMA : KVC_KERNEL_VALU;
+    if (kernel < KVC_KERNEL_AUTO || kernel > KVC_KERNEL_MFMA_BALANCED) return KVC_ERR_BAD_SHAPE;
+    if (kernel == KVC_KERNEL_AUTO)
+        kernel = balanced_ok(*d, max_ctx) ? KVC_KERNEL_MFMA_BALANCED
+                 : mfma_ok(*d)            ? KVC_KERNEL_MFMA
+                                          : KVC_KERNEL_VALU;
     if (kernel != KVC_KERNEL_VALU && !mfma_ok(*d)) return KVC_ERR_UNSUPPORTED;
+    if (kernel == KVC_KERNEL_MFMA_BALANCED && !balanced_ok(*d, max_ctx)) return KVC_ERR_UNSUPPORTED;
+
+    const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;
+    if (kernel == KVC_KERNEL_MFMA_BALANCED) {
+        // One wavefront per SIMD slot at 3 waves/SIMD; a wavefront never takes fewer than
+        // min_chunk tiles, which bounds the partials of a row (and the workspace) from the host.
+        const int64_t max_tiles = ceil_div(max_ctx, 16);
+        const int min_chunk = d->partition_tokens ? d->partition_tokens / 16
+                                                  : int(std::max<int64_t>(4, ceil_div(max_tiles, 32)));
+        const int64_t parts = ceil_div(max_tiles, min_chunk) + 1;
+        pl->kernel = kernel;
+        pl->partition_tokens = min_chunk * 16;
+        pl->min_chunk_tiles = min_chunk;
+        pl->max_partitions = int(parts);
+        pl->partial_grid = kvc::kNumCUs * 3;
+        pl->merge_grid = ceil_div(rows, kvc::kWaves);
+        pl->max_context_len = max_ctx;
+        const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);
+        pl->ml_offset = (acc + 255) & ~uint64_t(255);
+        pl->cnt_offset = (pl->ml_offset + uint64_t(rows) * parts * 2 * sizeof(float) + 255) & ~uint64_t(255);
+        pl->workspace_bytes = pl->cnt_offset + uint64_t(d->num_seqs) * d->num_kv_heads * sizeof(int32_t);
+        return KVC_OK;
+    }
 
     const int group = d->num_q_heads / d->num_kv_heads;
     const int64_t base_items = kernel == KVC_KERNEL_VALU
@@ -78,7 +112,6 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
         }
     }
     const int64_t parts = ceil_div(max_ctx, pt);
-    const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;
     if (base_items * parts > kMaxGrid || rows * parts > kMaxGrid) return KVC_ERR_BAD_SHAPE;
 
     pl->kernel = kernel;
@@ -87,12 +120,14 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
     pl->partial_grid = base_items * parts;
     pl->merge_grid = parts > 1 ? ceil_div(rows, kvc::kWaves) : 0;
     pl->max_context_len = max_ctx;
+    pl->min_chunk_tiles = 0;
+    pl->cnt_offset = 0;
     if (parts > 1) {
         const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);
-        pl->acc_bytes = (acc + 255) & ~uint64_t(255);
-        pl->workspace_bytes = pl->acc_bytes + uint64_t(rows) * parts * 2 * sizeof(float);
+        pl->ml_offset = (acc + 255) & ~uint64_t(255);
+        pl->workspace_bytes = pl->ml_offset + uint64_t(rows) * parts * 2 * sizeof(float);
     } else {
-        pl->acc_bytes = 0;
+        pl->ml_offset = 0;
         pl->workspace_bytes = 0;
     }
     return KVC_OK;
@@ -110,6 +145,7 @@ kvc::AttnParams make_params(const kvc_attn_desc &d, const Plan &pl, float scale)
     p.partition_tokens = pl.partition_tokens;
     p.max_partitions = pl.max_partitions;
     p.k_via_lds = pl.kernel == KVC_KERNEL_MFMA_LDS;
+    p.min_chunk_tiles = pl.min_chunk_tiles;
     p.scale = scale;
     p.scale_log2e = float(double(scale) * 1.4426950408889634);
     return p;
@@ -118,11 +154,13 @@ kvc::AttnParams make_params(const kvc_attn_desc &d, const Plan &pl, float scale)
 int check_workspace(const Plan &pl, void *workspace, size_t workspace_bytes, kvc::Workspace *ws) {
     ws->acc = nullptr;
     ws->ml = nullptr;
+    ws->cnt = nullptr;
     if (pl.workspace_bytes == 0) return KVC_OK;
     if (!workspace || workspace_bytes < pl.workspace_bytes) return KVC_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
     ws->acc = static_cast<float *>(workspace);
-    ws->ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.acc_bytes);
+    ws->ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
+    ws->cnt = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(workspace) + pl.cnt_offset);
     return KVC_OK;
 }
 
@@ -134,6 +172,9 @@ int run_partial(const void *q, const void *k_cache, const void *v_cache, const i
     if (pl.kernel == KVC_KERNEL_VALU)
         e = kvc::launch_partial_valu(q, k_cache, v_cache, block_tables, context_lens, out, ws, p,
                                      desc->dtype, desc->head_dim, int(pl.partial_grid), stream);
+    else if (pl.kernel == KVC_KERNEL_MFMA_BALANCED)
+        e = kvc::launch_partial_mfma_stream(q, k_cache, v_cache, block_tables, context_lens, out,
+                                            ws, p, int(pl.partial_grid), stream);
     else
         e = kvc::launch_partial_mfma(q, k_cache, v_cache, block_tables, context_lens, out, ws, p,
                                      int(pl.partial_grid), stream);
@@ -145,7 +186,9 @@ int run_merge(const int32_t *context_lens, void *out, const kvc_attn_desc *desc,
     if (pl.merge_grid == 0) return KVC_OK;
     const kvc::AttnParams p = make_params(*desc, pl, 1.0f);
     const hipError_t e = kvc::launch_merge(context_lens, out, ws, p, desc->dtype, desc->head_dim,
-                                           pl.kernel != KVC_KERNEL_VALU, int(pl.merge_grid), stream);
+                                           pl.kernel != KVC_KERNEL_VALU,
+                                           pl.kernel == KVC_KERNEL_MFMA_BALANCED, int(pl.merge_grid),
+                                           stream);
     return e == hipSuccess ? KVC_OK : hip_failed(e);
 }
 

@@ -20,20 +20,25 @@ struct AttnParams {
     int partition_tokens;   // split-K partition length, multiple of 16
     int max_partitions;     // partitions per sequence the grid and workspace provide for
     int k_via_lds;          // MFMA kernel: stage K tiles through LDS (1) or load them in operand layout (0)
+    int min_chunk_tiles;    // balanced kernel: smallest number of 16-token tiles a worker takes
     float scale;            // as given by the caller
     float scale_log2e;      // scale * log2(e), for the base-2 softmax of the MFMA kernel
 };
 
 // Workspace layout: acc [num_seqs][num_q_heads][max_partitions][head_dim] fp32, then
-// ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum) at a
-// 256-byte aligned offset.
+// ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum), then
+// (balanced kernel only) cnt [num_seqs][num_kv_heads] int32 = partials per row; each array
+// starts at a 256-byte aligned offset.
 struct Workspace {
     float *acc;
     float *ml;
+    int32_t *cnt;
 };
 
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup, every attention kernel
 constexpr int kWaves = kThreads / 64;
+constexpr int kNumCUs = 256;        // MI355X
+constexpr int kMaxStreamSeqs = 1024;  // batch limit of the balanced kernel (prefix sum lives in LDS)
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the
 // hipError_t of the launch.
@@ -44,8 +49,15 @@ hipError_t launch_partial_valu(const void *q, const void *k_cache, const void *v
 hipError_t launch_partial_mfma(const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens, void *out,
                                Workspace ws, const AttnParams &p, int grid, hipStream_t stream);
+hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const void *v_cache,
+                                      const int32_t *block_tables, const int32_t *context_lens,
+                                      void *out, Workspace ws, const AttnParams &p, int grid,
+                                      hipStream_t stream);
+// base2: partials are in base-2 units; counted: partial counts come from ws.cnt (balanced
+// kernel) instead of ceil(context_len / partition_tokens).
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
-                        int dtype, int head_dim, bool base2, int grid, hipStream_t stream);
+                        int dtype, int head_dim, bool base2, bool counted, int grid,
+                        hipStream_t stream);
 hipError_t launch_block_copy(const kvc_pool &src, const kvc_pool &dst, const int64_t *mapping,
                              int64_t num_pairs, hipStream_t stream);
 

@@ -1,13 +1,19 @@
 // Second pass of split-K paged decode attention (gfx950): combine the per-partition
 // (max, sum, un-normalised accumulator) triples of every (sequence, query head) whose
-// context spans more than one partition, normalise and cast.
+// context was split, normalise and cast.
 //
 //   M = max_p m_p;  out = sum_p w_p acc_p / sum_p w_p l_p,  w_p = exp(m_p - M)
 //
 // (exp is base 2 when the partial kernel worked in base-2 units.)  One wavefront per
-// (sequence, head); lanes stride over head_dim, so every workspace row is read with
-// coalesced 256/512-byte accesses.  Rows finished by the partial kernel (one partition)
-// and empty contexts are skipped.
+// (sequence, head).  Lane i first fetches (m, l) of partial i, so all weights of up to 64
+// partials come from one load and one wavefront max/sum; the accumulator rows are then
+// streamed with the weight broadcast from its lane, lanes striding over head_dim (coalesced
+// 256/512-byte reads, independent across partials so several are in flight).
+//
+// The number of partials of a row is ceil(context_len / partition_tokens) for the
+// fixed-partition kernels, or the count the balanced kernel left in the workspace.  Rows
+// finished by the partial kernel (one partial) are skipped; with the balanced kernel, rows
+// with an empty context are zeroed here.
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -25,7 +31,7 @@ __device__ inline uint16_t f32_to_bf16_rne(float x) {
 __device__ inline void store_out(float *o, float x) { *o = x; }
 __device__ inline void store_out(uint16_t *o, float x) { *o = f32_to_bf16_rne(x); }
 
-template <typename T, int D, bool BASE2>
+template <typename T, int D, bool BASE2, bool COUNTED>
 __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__restrict__ context_lens,
                                                             T *__restrict__ out, Workspace ws,
                                                             AttnParams p) {
@@ -35,11 +41,23 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
     if (row >= p.num_seqs * p.num_q_heads) return;
     const int seq = row / p.num_q_heads;
     const int ctx = context_lens[seq];
-    if (ctx <= p.partition_tokens) return;  // finished by the partial kernel (or empty)
-    const int nparts = min((ctx + p.partition_tokens - 1) / p.partition_tokens, p.max_partitions);
+    int nparts;
+    if (COUNTED) {
+        if (ctx <= 0) {
+#pragma unroll
+            for (int j = 0; j < DPL; ++j) store_out(out + size_t(row) * D + lane * DPL + j, 0.f);
+            return;
+        }
+        const int head = row - seq * p.num_q_heads;
+        nparts = ws.cnt[seq * p.num_kv_heads + head / p.group];
+    } else {
+        nparts = (ctx + p.partition_tokens - 1) / p.partition_tokens;  // <= 1: finished already, or empty
+    }
+    if (nparts <= 1) return;
+    nparts = min(nparts, p.max_partitions);
 
     const float *ml = ws.ml + size_t(row) * p.max_partitions * 2;
-    const float *acc = ws.acc + size_t(row) * p.max_partitions * D;
+    const float *acc = ws.acc + size_t(row) * p.max_partitions * D + lane * DPL;
 
     float M = -INFINITY;
     for (int i = lane; i < nparts; i += 64) M = fmaxf(M, ml[2 * i]);
@@ -49,36 +67,54 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
     float L = 0.f, a[DPL];
 #pragma unroll
     for (int j = 0; j < DPL; ++j) a[j] = 0.f;
-    for (int i = 0; i < nparts; ++i) {
-        const float x = ml[2 * i] - M;
-        const float w = BASE2 ? __builtin_amdgcn_exp2f(x) : expf(x);
-        L = fmaf(w, ml[2 * i + 1], L);
+    for (int c0 = 0; c0 < nparts; c0 += 64) {
+        const int i = c0 + lane;
+        float w = 0.f;
+        if (i < nparts) {
+            const float2 v = *reinterpret_cast<const float2 *>(ml + 2 * i);
+            const float x = v.x - M;
+            w = BASE2 ? __builtin_amdgcn_exp2f(x) : expf(x);
+            L = fmaf(w, v.y, L);
+        }
+        const int nt = min(64, nparts - c0);
+#pragma unroll 4
+        for (int t = 0; t < nt; ++t) {
+            const float wt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), t));
+            const float *src = acc + size_t(c0 + t) * D;
 #pragma unroll
-        for (int j = 0; j < DPL; ++j) a[j] = fmaf(w, acc[size_t(i) * D + lane * DPL + j], a[j]);
+            for (int j = 0; j < DPL; ++j) a[j] = fmaf(wt, src[j], a[j]);
+        }
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off);
 #pragma unroll
     for (int j = 0; j < DPL; ++j) store_out(out + size_t(row) * D + lane * DPL + j, a[j] / L);
 }
 
 template <typename T, int D>
-void launch(bool base2, const int32_t *cl, void *out, Workspace ws, const AttnParams &p, int grid,
-            hipStream_t stream) {
-    if (base2)
-        pa_merge_kernel<T, D, true><<<dim3(grid), dim3(kThreads), 0, stream>>>(cl, static_cast<T *>(out), ws, p);
+void launch(bool base2, bool counted, const int32_t *cl, void *out, Workspace ws, const AttnParams &p,
+            int grid, hipStream_t stream) {
+    T *o = static_cast<T *>(out);
+    const dim3 g(grid), b(kThreads);
+    if (counted)
+        pa_merge_kernel<T, D, true, true><<<g, b, 0, stream>>>(cl, o, ws, p);  // balanced kernel: always base 2
+    else if (base2)
+        pa_merge_kernel<T, D, true, false><<<g, b, 0, stream>>>(cl, o, ws, p);
     else
-        pa_merge_kernel<T, D, false><<<dim3(grid), dim3(kThreads), 0, stream>>>(cl, static_cast<T *>(out), ws, p);
+        pa_merge_kernel<T, D, false, false><<<g, b, 0, stream>>>(cl, o, ws, p);
 }
 
 }  // namespace
 
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
-                        int dtype, int head_dim, bool base2, int grid, hipStream_t stream) {
+                        int dtype, int head_dim, bool base2, bool counted, int grid,
+                        hipStream_t stream) {
     if (dtype == KVC_F32) {
-        if (head_dim == 64) launch<float, 64>(base2, context_lens, out, ws, p, grid, stream);
-        else launch<float, 128>(base2, context_lens, out, ws, p, grid, stream);
+        if (head_dim == 64) launch<float, 64>(base2, counted, context_lens, out, ws, p, grid, stream);
+        else launch<float, 128>(base2, counted, context_lens, out, ws, p, grid, stream);
     } else {
-        if (head_dim == 64) launch<uint16_t, 64>(base2, context_lens, out, ws, p, grid, stream);
-        else launch<uint16_t, 128>(base2, context_lens, out, ws, p, grid, stream);
+        if (head_dim == 64) launch<uint16_t, 64>(base2, counted, context_lens, out, ws, p, grid, stream);
+        else launch<uint16_t, 128>(base2, counted, context_lens, out, ws, p, grid, stream);
     }
     return hipGetLastError();
 }

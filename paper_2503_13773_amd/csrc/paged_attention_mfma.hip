@@ -1,62 +1,27 @@
-// Split-K partial kernel of paged decode attention on the matrix cores (gfx950, bf16,
-// head_dim 128, block_size a multiple of 16, up to 16 query heads per KV head).
+// Split-K partial kernel of paged decode attention on the matrix cores with FIXED-LENGTH
+// partitions (gfx950, bf16, head_dim 128, block_size a multiple of 16, up to 16 query heads
+// per KV head).
 //
 // One workgroup = one (sequence, KV head, partition of the context); all query heads that
 // share the KV head ride along as the 16 columns of an MFMA tile, so K and V are read from
 // HBM exactly once per KV head (grouped-query heads form a real dense tile: 16 tokens x
 // 128 dims x G heads).  The four wavefronts take 16-token tiles round-robin, each with its
-// own online softmax; they are merged through LDS at the end.
+// own online softmax; they are merged through LDS at the end.  The per-tile arithmetic is
+// in pa_mfma_tile.h.
 //
-// Per 16-token tile and wavefront (lane = 16*quad + r):
-//   S[token][head]   = K[16 x 128] . Q^T[128 x 16]      4 x v_mfma_f32_16x16x32_bf16
-//       A operand: lane holds K[token r][32j + 8*quad .. +7]; B operand: the same dims of
-//       Q[head r].  K reaches that layout either straight from HBM (16 rows x 64 bytes per
-//       load instruction) or, in the LDS-staged variant, by fully coalesced 1 KiB loads, a
-//       16-byte XOR-swizzled write to LDS and a conflict-free 16-byte read back.
-//   softmax over the C layout: lane holds S[token 4*quad + i][head r], i < 4; the max over
-//       tokens is 3 in-lane max + 2 cross-quad shuffles.  exp2 with scale*log2(e) folded in.
-//   O^T[dim][head]  += V^T[128 x 16] . P^T[16 x 16]      8 x v_mfma_f32_16x16x16_bf16
-//       B operand P^T is exactly the C layout of S (tokens 4*quad + i, head r): no data
-//       movement.  A operand needs 4 tokens of one dim per lane; V is loaded row-wise (lane
-//       reads 16 bytes = dims 8r..8r+7 of tokens 4*quad + i: full 256-byte rows per 16
-//       lanes, coalesced) and the 4x8 patch is transposed in registers with 16 v_perm_b32.
-//       MFMA e then yields dims {8*row + e}: lane ends up with O[head r][32*quad .. +31].
-//   Every quantity attached to a head (max, sum, rescale factor, accumulator) lives in the
-//   lanes with that r, so the online-softmax rescale needs no cross-lane traffic.
-//
-// Softmax weights are rounded to bf16 for the P.V product and the normaliser sums the
-// *rounded* weights, so weights still sum to one.  Rows past the context in the last tile
-// get score -inf and their V data is zeroed (NaN there cannot leak).
+// K reaches the MFMA operand layout either straight from HBM (KLDS = false) or by fully
+// coalesced 1 KiB loads, a 16-byte XOR-swizzled write to LDS and a conflict-free 16-byte
+// read back (KLDS = true).
 #include <math.h>
 
 #include "kvc_internal.h"
+#include "pa_mfma_tile.h"
 
 namespace kvc {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-constexpr int D = 128;
-constexpr int kTileTokens = 16;
-constexpr int kTileElems = kTileTokens * D;  // 2048 bf16 = 4 KiB
-
-__device__ inline uint16_t f32_to_bf16_rne(float x) {
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return uint16_t(u >> 16);
-}
-
-// two fp32 -> packed bf16 pair (round to nearest even), low half = a
-__device__ inline uint32_t pack_bf16(float a, float b) {
-    const floatx2 f = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-}
+using namespace mfma;
 
 template <int GP, bool KLDS>
 __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
@@ -106,23 +71,11 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
     int my_blk = 0;
     if (lane < my_n) my_blk = table[(tile0 + wave + kWaves * lane) >> tiles_per_block_log2];
 
-    // Q as the B operand of S = K.Q^T: lane (quad, r) holds Q[head r][32j + 8*quad .. +7]
     bf16x8 qb[4];
-    {
-        const uint4 zero = {0u, 0u, 0u, 0u};
-        const uint16_t *qrow = q + (size_t(seq) * p.num_q_heads + head0 + r) * D + 8 * quad;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint4 w = zero;
-            if (r < G) w = *reinterpret_cast<const uint4 *>(qrow + 32 * j);
-            qb[j] = __builtin_bit_cast(bf16x8, w);
-        }
-    }
+    load_q_operand(qb, q + (size_t(seq) * p.num_q_heads + head0 + (r < G ? r : 0)) * D, quad, r < G);
 
-    floatx4 acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
+    HeadState st;
+    st.reset();
 
     const size_t head_elems = size_t(p.block_size) * D;
     const size_t block_elems = head_elems * p.num_kv_heads;
@@ -165,59 +118,7 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
         }
-
-        floatx4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j], qb[j], s, 0, 0, 0);
-
-        const int trow = gt * kTileTokens + 4 * quad;  // token of s[0]
-        float sv[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sv[i] = s[i] * p.scale_log2e;
-        if ((gt + 1) * kTileTokens > tok1) {  // ragged last tile (wavefront-uniform)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (trow + i >= tok1) {
-                    sv[i] = -INFINITY;
-                    vr[i] = uint4{0u, 0u, 0u, 0u};
-                }
-            }
-        }
-        float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx);  // finite: every tile has at least one valid token
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        float pf[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pf[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
-        const uint32_t p01 = pack_bf16(pf[0], pf[1]);
-        const uint32_t p23 = pack_bf16(pf[2], pf[3]);
-        const float psum = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
-                           (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
-        l = fmaf(l, alpha, psum);
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] *= alpha;
-        }
-        const uint2 pw = {p01, p23};
-        const shortx4 pb = __builtin_bit_cast(shortx4, pw);
-
-        const uint32_t v0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
-        const uint32_t v1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
-        const uint32_t v2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
-        const uint32_t v3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            // dword w of a row holds dims 8r+2w (low half) and 8r+2w+1 (high half)
-            const uint2 lo = {__builtin_amdgcn_perm(v1[w], v0[w], 0x05040100u),
-                              __builtin_amdgcn_perm(v3[w], v2[w], 0x05040100u)};
-            const uint2 hi = {__builtin_amdgcn_perm(v1[w], v0[w], 0x07060302u),
-                              __builtin_amdgcn_perm(v3[w], v2[w], 0x07060302u)};
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, lo), pb, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, hi), pb, acc[2 * w + 1], 0, 0, 0);
-        }
+        compute_tile(st, ka, vr, qb, p.scale_log2e, tok1 - gt * kTileTokens, quad);
     };
 
     uint4 kA[4], vA[4], kB[4], vB[4];
@@ -232,9 +133,7 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
         }
     }
 
-    // per-head sum over the 4 quads (the max is already common to them)
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    st.finish();
 
     float *sm_acc = reinterpret_cast<float *>(smem);  // [kWaves][GP][D]
     float *sm_m = sm_acc + kAccFloats;                // [kWaves][16]
@@ -244,12 +143,12 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
         float *dst = sm_acc + (size_t(wave) * GP + r) * D + 32 * quad;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<float4 *>(dst + 8 * i) = float4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-            *reinterpret_cast<float4 *>(dst + 8 * i + 4) = float4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+            *reinterpret_cast<float4 *>(dst + 8 * i) = float4{st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]};
+            *reinterpret_cast<float4 *>(dst + 8 * i + 4) = float4{st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]};
         }
         if (quad == 0) {
-            sm_m[wave * 16 + r] = m;
-            sm_l[wave * 16 + r] = l;
+            sm_m[wave * 16 + r] = st.m;
+            sm_l[wave * 16 + r] = st.l;
         }
     }
     __syncthreads();

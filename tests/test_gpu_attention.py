@@ -13,7 +13,7 @@ from gpu_util import BF16_TOL, F32_TOL, dev_tensor, out_bits, out_to_f64, run_gp
 
 pytestmark = pytest.mark.gpu
 
-VALU, MFMA, MFMA_LDS = 1, 2, 3
+VALU, MFMA, MFMA_LDS, BALANCED = 1, 2, 3, 4
 
 
 def check(w, oracle_mod, label, **opts):
@@ -46,7 +46,7 @@ def test_cfg1_tiny_fp32(oracle_mod):
     check(w, oracle_mod, "cfg1 loose bound", tight=False)
 
 
-@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS, BALANCED])
 @pytest.mark.parametrize("name,nseq,scale", [("cfg2", 6, 0.5), ("cfg3", 12, 0.5), ("cfg4", 2, 0.04),
                                              ("cfg5", 16, 0.5)])
 def test_configs_small_every_element(oracle_mod, name, nseq, scale, kernel):
@@ -81,7 +81,7 @@ def test_configs_full_size_sampled_rows(oracle_mod, name):
 # ---------------------------------------------------------------------------
 # shapes, tails and degenerate cases
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS, BALANCED])
 def test_ragged_tails_and_partition_edges(oracle_mod, kernel):
     lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513]
     w = custom(101, dtype=W.BF16, lens=lens, hq=8, hkv=2, d=128, bs=16)
@@ -89,10 +89,24 @@ def test_ragged_tails_and_partition_edges(oracle_mod, kernel):
         check(w, oracle_mod, f"tails pt={pt}", kernel=kernel, partition_tokens=pt)
 
 
+@pytest.mark.parametrize("hkv", [1, 2, 8])
+def test_balanced_ranges_cross_rows_and_skip_empty_sequences(oracle_mod, hkv):
+    """Worker ranges of the balanced kernel start and end inside rows, span several short rows
+    and step over empty sequences (also at both ends of the batch)."""
+    lens = [0, 0, 5, 16, 17, 0, 33, 1, 250, 0, 0, 47, 48, 49, 700, 3, 0, 90, 16, 0]
+    w = custom(120 + hkv, dtype=W.BF16, lens=lens, hq=2 * hkv, hkv=hkv, d=128, bs=16)
+    w.block_tables[np.asarray(lens) == 0, :] = -1
+    for chunk_tokens in (16, 48, 80, 112, 176, 1024):
+        check(w, oracle_mod, f"balanced chunk={chunk_tokens}", kernel=BALANCED,
+              partition_tokens=chunk_tokens)
+    w2 = custom(130 + hkv, dtype=W.BF16, lens=[0, 0, 0], hq=2 * hkv, hkv=hkv, d=128, bs=16)
+    check(w2, oracle_mod, "balanced all empty", kernel=BALANCED)
+
+
 @pytest.mark.parametrize("hq,hkv", [(1, 1), (2, 1), (3, 1), (4, 1), (8, 1), (16, 1), (12, 4), (5, 5), (40, 8)])
 def test_group_sizes(oracle_mod, hq, hkv):
     w = custom(102, dtype=W.BF16, lens=[40, 200, 77], hq=hq, hkv=hkv, d=128, bs=16)
-    for kernel in (VALU, MFMA, MFMA_LDS):
+    for kernel in (VALU, MFMA, MFMA_LDS, BALANCED):
         check(w, oracle_mod, f"group {hq}/{hkv}", kernel=kernel, partition_tokens=64)
 
 
@@ -103,8 +117,9 @@ def test_group_larger_than_16_takes_valu(oracle_mod):
     desc = K.attn_desc(d["q"], d["k"], d["tables"])
     assert K.attn_plan(desc).kernel == VALU
     check(w, oracle_mod, "group 32")
-    with pytest.raises(K.KvcError):
-        run_gpu(w, kernel=MFMA)
+    for kernel in (MFMA, BALANCED):
+        with pytest.raises(K.KvcError):
+            run_gpu(w, kernel=kernel)
 
 
 @pytest.mark.parametrize("bs", [1, 2, 4, 8, 16, 32, 64])
@@ -114,6 +129,7 @@ def test_block_sizes(oracle_mod, bs):
     if bs >= 16:
         check(w, oracle_mod, f"bs={bs} mfma", kernel=MFMA, partition_tokens=64)
         check(w, oracle_mod, f"bs={bs} mfma lds", kernel=MFMA_LDS, partition_tokens=64)
+        check(w, oracle_mod, f"bs={bs} balanced", kernel=BALANCED, partition_tokens=16)
     wf = custom(105, dtype=W.F32, lens=[5, 70, 131], hq=4, hkv=2, d=64, bs=bs)
     check(wf, oracle_mod, f"bs={bs} f32", partition_tokens=32)
 
@@ -130,13 +146,13 @@ def test_fp32_long_context_stays_within_1e5(oracle_mod):
     assert check(w, oracle_mod, "f32 long") <= F32_TOL
 
 
-@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS, BALANCED])
 def test_maximum_partition_length(oracle_mod, kernel):
     w = custom(108, dtype=W.BF16, lens=[4096, 4095, 8200], hq=4, hkv=1, d=128, bs=16)
     check(w, oracle_mod, "pt=4096", kernel=kernel, partition_tokens=4096)
 
 
-@pytest.mark.parametrize("dtype,kernels", [(W.F32, [VALU]), (W.BF16, [VALU, MFMA, MFMA_LDS])])
+@pytest.mark.parametrize("dtype,kernels", [(W.F32, [VALU]), (W.BF16, [VALU, MFMA, MFMA_LDS, BALANCED])])
 def test_context_one_returns_v_bit_exactly(dtype, kernels):
     d_ = 64 if dtype == W.F32 else 128
     w = custom(109, dtype=dtype, lens=[1, 1, 1, 1], hq=8, hkv=2, d=d_, bs=16)
@@ -157,7 +173,7 @@ def test_context_zero_gives_zeros_and_leaves_neighbours_alone(oracle_mod, dtype)
     d_ = 64 if dtype == W.F32 else 128
     w = custom(110, dtype=dtype, lens=[0, 37, 0, 300, 0], hq=4, hkv=2, d=d_, bs=16)
     w.block_tables[[0, 2, 4], :] = -1
-    kernels = [VALU] if dtype == W.F32 else [VALU, MFMA, MFMA_LDS]
+    kernels = [VALU] if dtype == W.F32 else [VALU, MFMA, MFMA_LDS, BALANCED]
     ref = oracle_mod.attention_of_workload(w)
     for kernel in kernels:
         for pt in (0, 64):
@@ -171,7 +187,7 @@ def test_context_zero_gives_zeros_and_leaves_neighbours_alone(oracle_mod, dtype)
             assert np.abs(got - ref).max() <= tol_of(w)
 
 
-@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS, BALANCED])
 def test_poison_beyond_context_and_in_unused_entries(oracle_mod, kernel):
     """NaN in slots past the context, in unused blocks; -1 / huge ids in unused table entries."""
     w = custom(111, dtype=W.BF16, lens=[5, 16, 17, 100, 250, 1], hq=8, hkv=2, d=128, bs=16, nb_extra=9)
@@ -193,7 +209,7 @@ def test_poison_beyond_context_and_in_unused_entries(oracle_mod, kernel):
     check(w, oracle_mod, "poisoned", kernel=kernel, partition_tokens=64)
 
 
-@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS])
+@pytest.mark.parametrize("kernel", [VALU, MFMA, MFMA_LDS, BALANCED])
 def test_placement_invariance_is_bitwise_on_gpu(kernel):
     """Same logical KV at another physical placement / pool size: identical output bits."""
     w = custom(112, dtype=W.BF16, lens=[70, 300, 33], hq=8, hkv=2, d=128, bs=16)
