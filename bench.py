@@ -4,8 +4,10 @@
 A step = one pass of the whole hot path over one synthetic batch, all inputs resident in
 HBM: paged_attention_decode (split-K partial kernel + merge kernel) over the batch, then
 kv_block_copy swapping the K and V blocks of 20 % of the batch's sequences out to a second
-device pool.  Successive steps rotate over replicas of the batch at different addresses
-(>= 2 GiB in total) so that the 256 MB memory-side cache cannot serve the KV reads.
+device pool.  Successive steps rotate over replicas of the KV pools at different addresses
+(>= 2 GiB in total), the way successive layers of a model each own a KV pool, so that the
+256 MB memory-side cache cannot serve the KV reads.  Block tables, context lengths and the
+copy mapping are shared by the replicas, as they are shared by the layers of one decode step.
 
 Prints ONE JSON line: whole-step throughput in algorithmic GB/s, the roofline record of the
 dominant kernel (the attention partial kernel, timed per launch with HIP events on the
@@ -47,7 +49,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg3b", choices=sorted(WORKLOADS))
-    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA, 3 MFMA with LDS-staged K")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA fixed partitions, 3 same with LDS-staged K, 4 MFMA balanced")
     ap.add_argument("--partition-tokens", type=int, default=0)
     ap.add_argument("--replica-bytes", type=float, default=2.2e9,
                     help="rotate over replicas of the batch totalling at least this many KV bytes")
@@ -109,8 +111,8 @@ def main() -> int:
     for r in range(n_rep):
         pool1 = base_pool if r == 0 else base_pool.clone()
         rep = dict(pool1=pool1, k=pool1[0], v=pool1[1],
-                   q=base["q"].clone(), tables=base["tables"].clone(), lens=base["lens"].clone(),
-                   mapping=base["mapping"].clone(), out=torch.empty_like(base["q"]),
+                   q=base["q"].clone(), tables=base["tables"], lens=base["lens"],
+                   mapping=base["mapping"], out=torch.empty_like(base["q"]),
                    ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda"),
                    pool2=torch.zeros((2, pool2_blocks) + tuple(pool1.shape[2:]), dtype=pool1.dtype,
                                      device="cuda"))
@@ -162,8 +164,23 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / steps
 
+    def timed_region(fn, steps, warmup):
+        """Average duration of one fn launch: HIP events on the launch stream around `steps`
+        back-to-back launches."""
+        for i in range(warmup):
+            fn(reps[i % n_rep])
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for i in range(steps):
+            fn(reps[i % n_rep])
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / steps
+
     def timed_events(fn, steps, warmup, hot=False):
-        """Average duration of one fn launch, HIP events on the launch stream around each call."""
+        """Duration of single fn launches, HIP events on the launch stream around each call
+        (includes the event overhead of a few microseconds)."""
         pick = (lambda i: reps[0]) if hot else (lambda i: reps[i % n_rep])
         for i in range(warmup):
             fn(pick(i))
@@ -181,11 +198,16 @@ def main() -> int:
     K_, W_ = args.steps, args.warmup
     step_s = timed_wall(step, K_, W_)                      # the headline: exactly K steps, wall clock
     attn_avg, attn_med, attn_p10, attn_p90 = timed_events(attn, K_, W_)
-    part_avg, part_med, _, _ = timed_events(partial, K_, W_)
+    part_pair_avg, part_med, _, _ = timed_events(partial, K_, W_)
+    part_avg = timed_region(partial, K_, W_)
+    attn_region = timed_region(attn, K_, W_)
+    copy_region = timed_region(copy, K_, W_)
     copy_avg, copy_med, _, _ = timed_events(copy, K_, W_)
     hot_avg, hot_med, _, _ = timed_events(attn, K_, W_, hot=True)
     log(f"[bench] step {step_s*1e6:.1f} us | attention avg {attn_avg*1e6:.1f} med {attn_med*1e6:.1f} us "
-        f"(hot {hot_med*1e6:.1f}) | partial kernel avg {part_avg*1e6:.1f} us | copy avg {copy_avg*1e6:.1f} us")
+        f"(hot {hot_med*1e6:.1f}) | partial kernel {part_avg*1e6:.1f} us back-to-back, {part_pair_avg*1e6:.1f} us "
+        f"event pairs | attention back-to-back {attn_region*1e6:.1f} us | copy avg {copy_avg*1e6:.1f} us, "
+        f"back-to-back {copy_region*1e6:.1f} us")
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, same inputs ----
     cpu = None
@@ -244,6 +266,9 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "detail": {
             "step_bytes": int(step_bytes), "attention_bytes": int(attn_bytes), "copy_bytes": int(copy_bytes),
+            "attention_us_back_to_back": round(attn_region * 1e6, 2),
+            "copy_us_back_to_back": round(copy_region * 1e6, 2),
+            "partial_kernel_us_event_pairs": round(part_pair_avg * 1e6, 2),
             "attention_us": round(attn_avg * 1e6, 2), "attention_us_median": round(attn_med * 1e6, 2),
             "attention_us_p10": round(attn_p10 * 1e6, 2), "attention_us_p90": round(attn_p90 * 1e6, 2),
             "attention_GBs": round(attn_bytes / attn_avg / 1e9, 1),
@@ -252,7 +277,7 @@ def main() -> int:
             "tokens_per_s": round(w.num_seqs / attn_avg, 1),
             "copy_us": round(copy_avg * 1e6, 2), "copy_GBs": round(copy_bytes / copy_avg / 1e9, 1),
         },
-        "roofline": {"bound": "hbm", "kernel": "pa_partial_mfma_kernel" if plan.kernel != 1 else "pa_partial_valu_kernel",
+        "roofline": {"bound": "hbm", "kernel": {1: "pa_partial_valu_kernel", 2: "pa_partial_mfma_kernel", 3: "pa_partial_mfma_kernel", 4: "pa_stream_mfma_kernel"}[int(plan.kernel)],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "bytes_per_launch": int(part_bytes), "avg_launch_us": round(part_avg * 1e6, 2)},

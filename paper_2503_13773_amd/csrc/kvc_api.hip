@@ -76,8 +76,8 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
 
     const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;
     if (kernel == KVC_KERNEL_MFMA_BALANCED) {
-        // One wavefront per SIMD slot at 3 waves/SIMD; a wavefront never takes fewer than
-        // min_chunk tiles, which bounds the partials of a row (and the workspace) from the host.
+        // A wavefront never takes fewer than min_chunk tiles, which bounds the partials of a row
+        // (and the workspace) from the host.
         const int64_t max_tiles = ceil_div(max_ctx, 16);
         const int min_chunk = d->partition_tokens ? d->partition_tokens / 16
                                                   : int(std::max<int64_t>(4, ceil_div(max_tiles, 32)));
@@ -86,7 +86,11 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
         pl->partition_tokens = min_chunk * 16;
         pl->min_chunk_tiles = min_chunk;
         pl->max_partitions = int(parts);
-        pl->partial_grid = kvc::kNumCUs * 3;
+#ifdef KVC_PROBE_WGS_PER_CU
+        pl->partial_grid = kvc::kNumCUs * KVC_PROBE_WGS_PER_CU;
+#else
+        pl->partial_grid = kvc::kNumCUs;  // 4 wavefronts per CU: one worker per SIMD
+#endif
         pl->merge_grid = ceil_div(rows, kvc::kWaves);
         pl->max_context_len = max_ctx;
         const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);

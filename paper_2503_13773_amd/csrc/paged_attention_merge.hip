@@ -6,9 +6,10 @@
 //
 // (exp is base 2 when the partial kernel worked in base-2 units.)  One wavefront per
 // (sequence, head).  Lane i first fetches (m, l) of partial i, so all weights of up to 64
-// partials come from one load and one wavefront max/sum; the accumulator rows are then
-// streamed with the weight broadcast from its lane, lanes striding over head_dim (coalesced
-// 256/512-byte reads, independent across partials so several are in flight).
+// partials come from one load and one wavefront max/sum; that load is issued speculatively
+// together with the loads of the context length and the partial count, so the kernel is two
+// memory round trips deep.  The accumulator rows are then streamed with the weight broadcast
+// from its lane, lanes striding over head_dim (coalesced 256/512-byte reads, 8 rows in flight).
 //
 // The number of partials of a row is ceil(context_len / partition_tokens) for the
 // fixed-partition kernels, or the count the balanced kernel left in the workspace.  Rows
@@ -40,27 +41,31 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
     const int row = blockIdx.x * kWaves + wave;  // seq * num_q_heads + head
     if (row >= p.num_seqs * p.num_q_heads) return;
     const int seq = row / p.num_q_heads;
+    const int head = row - seq * p.num_q_heads;
+    const float *ml = ws.ml + size_t(row) * p.max_partitions * 2;
+    const float *acc = ws.acc + size_t(row) * p.max_partitions * D + lane * DPL;
+
+    // Three independent loads go out together: the context length, the partial count and
+    // (speculatively, whatever the slots hold) the (max, sum) pairs of the first 64 slots.
     const int ctx = context_lens[seq];
-    int nparts;
+    int nparts = COUNTED ? ws.cnt[seq * p.num_kv_heads + head / p.group] : 0;
+    float2 ml0 = float2{-INFINITY, 0.f};
+    if (lane < p.max_partitions) ml0 = *reinterpret_cast<const float2 *>(ml + 2 * lane);
+
     if (COUNTED) {
         if (ctx <= 0) {
 #pragma unroll
             for (int j = 0; j < DPL; ++j) store_out(out + size_t(row) * D + lane * DPL + j, 0.f);
             return;
         }
-        const int head = row - seq * p.num_q_heads;
-        nparts = ws.cnt[seq * p.num_kv_heads + head / p.group];
     } else {
         nparts = (ctx + p.partition_tokens - 1) / p.partition_tokens;  // <= 1: finished already, or empty
     }
     if (nparts <= 1) return;
     nparts = min(nparts, p.max_partitions);
 
-    const float *ml = ws.ml + size_t(row) * p.max_partitions * 2;
-    const float *acc = ws.acc + size_t(row) * p.max_partitions * D + lane * DPL;
-
-    float M = -INFINITY;
-    for (int i = lane; i < nparts; i += 64) M = fmaxf(M, ml[2 * i]);
+    float M = lane < nparts ? ml0.x : -INFINITY;
+    for (int i = lane + 64; i < nparts; i += 64) M = fmaxf(M, ml[2 * i]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
 
@@ -71,18 +76,30 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
         const int i = c0 + lane;
         float w = 0.f;
         if (i < nparts) {
-            const float2 v = *reinterpret_cast<const float2 *>(ml + 2 * i);
+            const float2 v = c0 == 0 ? ml0 : *reinterpret_cast<const float2 *>(ml + 2 * i);
             const float x = v.x - M;
             w = BASE2 ? __builtin_amdgcn_exp2f(x) : expf(x);
             L = fmaf(w, v.y, L);
         }
         const int nt = min(64, nparts - c0);
-#pragma unroll 4
-        for (int t = 0; t < nt; ++t) {
-            const float wt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), t));
-            const float *src = acc + size_t(c0 + t) * D;
+        int t = 0;
+        for (; t + 8 <= nt; t += 8) {  // 8 accumulator rows in flight
+            float x[8][DPL];
 #pragma unroll
-            for (int j = 0; j < DPL; ++j) a[j] = fmaf(wt, src[j], a[j]);
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int j = 0; j < DPL; ++j) x[u][j] = acc[size_t(c0 + t + u) * D + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), t + u));
+#pragma unroll
+                for (int j = 0; j < DPL; ++j) a[j] = fmaf(wt, x[u][j], a[j]);
+            }
+        }
+        for (; t < nt; ++t) {
+            const float wt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), t));
+#pragma unroll
+            for (int j = 0; j < DPL; ++j) a[j] = fmaf(wt, acc[size_t(c0 + t) * D + j], a[j]);
         }
     }
 #pragma unroll

@@ -121,15 +121,24 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
         compute_tile(st, ka, vr, qb, p.scale_log2e, tok1 - gt * kTileTokens, quad);
     };
 
+    // Two register sets, software-pipelined; the steady-state loop is branch-free so that the
+    // compiler's wait counts keep the 8 newest loads in flight, the 1- or 2-tile tail is peeled.
     uint4 kA[4], vA[4], kB[4], vB[4];
-    if (my_n > 0) issue(kA, vA, 0);
-    for (int it = 0; it < my_n; it += 2) {
-        const bool has1 = it + 1 < my_n;
-        if (has1) issue(kB, vB, it + 1);
-        compute(kA, vA, it);
-        if (has1) {
-            if (it + 2 < my_n) issue(kA, vA, it + 2);
+    if (my_n > 0) {
+        issue(kA, vA, 0);
+        int it = 0;
+        for (; it + 2 < my_n; it += 2) {
+            issue(kB, vB, it + 1);
+            compute(kA, vA, it);
+            issue(kA, vA, it + 2);
             compute(kB, vB, it + 1);
+        }
+        if (it + 1 < my_n) {
+            issue(kB, vB, it + 1);
+            compute(kA, vA, it);
+            compute(kB, vB, it + 1);
+        } else {
+            compute(kA, vA, it);
         }
     }
 

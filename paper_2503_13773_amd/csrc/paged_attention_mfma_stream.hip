@@ -8,16 +8,29 @@
 //
 //   rows  = (sequence n, KV head g), each with t_n = ceil(context_len_n / 16) tiles
 //   flat  = [row 0 tiles][row 1 tiles]...   T = num_kv_heads * sum_n t_n tiles in all
-//   every WAVEFRONT of the (fixed-size, one-wave-per-SIMD-slot) grid is a worker that takes
-//   C = max(C_min, ceil(T / workers)) consecutive flat tiles.
+//   every WAVEFRONT of the grid is a worker that takes C = max(C_min, ceil(T / workers))
+//   consecutive flat tiles.
+//
+// The grid is ONE wavefront per SIMD (256 CUs x 4).  Measured on MI355X: with 2 or 3
+// wavefronts per SIMD the older wavefronts win the memory-issue arbitration, the younger
+// ones starve until the older exit, and the kernel ends with a long, thinly populated
+// tail; one wavefront per SIMD with its loads kept in flight across row changes streams at
+// the same rate and all workers finish within a few percent of each other.
 //
 // A worker's range may start and end inside a row; each (row, tile range) it covers is a
 // "segment".  A segment that is a whole row is normalised and written to `out`; otherwise
 // the worker writes (max, sum, accumulator) to partial slot (worker - first worker of the
 // row), and the worker that owns tile 0 of a row records how many partials the row has.  The
-// merge kernel reads that count.  Wavefronts never synchronise with each other: no LDS
-// reduction, no barrier after the start-up prefix sum, and every loop is bounded by the
-// worker's static range, so every wavefront exits.
+// merge kernel reads that count.  Wavefronts never synchronise with each other after the
+// start-up prefix sum, and every loop is bounded by the worker's static range, so every
+// wavefront exits.
+//
+// The worker's tiles form one continuous stream, software-pipelined over two register sets:
+// the loads of tile i+1 are issued before tile i is consumed, also when tile i+1 belongs to
+// the next row.  An "issue cursor" (row, tile, block ids) runs one tile ahead of the
+// "compute cursor" (row, tile, softmax state, Q operand); block ids and the Q operand of
+// the row after the current one are prefetched when a cursor enters a row, so a row change
+// costs no dependent-load bubble.
 //
 // Start-up (once per workgroup): prefix sum of t_n over the batch in LDS (<= 1024 sequences),
 // then a binary search places each worker.  Per tile the arithmetic is pa_mfma_tile.h.
@@ -34,12 +47,21 @@ using namespace mfma;
 
 __device__ inline int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-__global__ __launch_bounds__(kThreads, 3) void pa_stream_mfma_kernel(
+// A row of the flattened work: (sequence, KV head); all fields wavefront-uniform.
+struct RowCursor {
+    int n;       // sequence
+    int kvh;     // KV head
+    int pref;    // tiles of all sequences before n
+    int tiles;   // t_n
+};
+
+__global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
     AttnParams p, int tiles_per_block_log2) {
-    __shared__ int s_pref[kMaxStreamSeqs + 1];  // exclusive prefix of tiles per sequence
+    __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of tiles per sequence (+ guard)
+    __shared__ int s_ctx[kMaxStreamSeqs];       // context length per sequence
     __shared__ int s_wave_tot[kWaves];
 
     const int tid = threadIdx.x;
@@ -55,7 +77,11 @@ __global__ __launch_bounds__(kThreads, 3) void pa_stream_mfma_kernel(
         for (int i = 0; i < 4; ++i) {
             const int n = tid * spt + i;
             int t = 0;
-            if (i < spt && n < nseq) t = (max(context_lens[n], 0) + kTileTokens - 1) >> 4;
+            if (i < spt && n < nseq) {
+                const int c = max(context_lens[n], 0);
+                s_ctx[n] = c;
+                t = (c + kTileTokens - 1) >> 4;
+            }
             local[i] = sum;
             sum += t;
         }
@@ -75,7 +101,10 @@ __global__ __launch_bounds__(kThreads, 3) void pa_stream_mfma_kernel(
             const int n = tid * spt + i;
             if (i < spt && n < nseq) s_pref[n] = excl + local[i];
         }
-        if (tid == kThreads - 1) s_pref[nseq] = excl + sum;
+        if (tid == kThreads - 1) {
+            s_pref[nseq] = excl + sum;
+            s_pref[nseq + 1] = excl + sum + 1;  // guard: "sequence nseq" looks non-empty, stops row walks
+        }
         __syncthreads();
     }
 
@@ -87,79 +116,99 @@ __global__ __launch_bounds__(kThreads, 3) void pa_stream_mfma_kernel(
     const int worker = blockIdx.x * kWaves + wave;
     if (int64_t(worker) * C >= T) return;
     const int f0 = worker * C;
-    const int f1 = min(T, f0 + C);
+    const int NT = min(T, f0 + C) - f0;  // tiles of this worker, >= 1
+
+    const size_t head_elems = size_t(p.block_size) * D;
+    const size_t block_elems = head_elems * Hkv;
+    const int sub_mask = (1 << tiles_per_block_log2) - 1;
+
+    // Row after `c` in flat order, skipping empty sequences.  Past the last row it parks on
+    // the guard entry (n == nseq), which is never dereferenced: a cursor only moves there
+    // when the worker has no tile left.
+    auto next_row = [&](const RowCursor &c) __attribute__((always_inline)) {
+        RowCursor o = c;
+        if (o.n < nseq && ++o.kvh == Hkv) {
+            o.kvh = 0;
+            do { ++o.n; } while (uniform(s_pref[o.n + 1]) == uniform(s_pref[o.n]));
+            o.pref = uniform(s_pref[o.n]);
+            o.tiles = uniform(s_pref[o.n + 1]) - o.pref;
+        }
+        return o;
+    };
+    // Block ids of tiles [first, first + 64) of a row, one per lane (entries past the row's
+    // last tile are not read).
+    auto load_blocks = [&](const RowCursor &c, int first) __attribute__((always_inline)) {
+        int b = 0;
+        if (c.n < nseq && first + lane < c.tiles)
+            b = block_tables[size_t(c.n) * p.max_blocks_per_seq + ((first + lane) >> tiles_per_block_log2)];
+        return b;
+    };
+    auto load_q = [&](bf16x8(&qb)[4], const RowCursor &c) __attribute__((always_inline)) {
+        const bool active = r < G && c.n < nseq;
+        const int n = c.n < nseq ? c.n : 0;
+        load_q_operand(qb, q + (size_t(n) * p.num_q_heads + c.kvh * G + (r < G ? r : 0)) * D, quad, active);
+    };
 
     // ---- place the worker: largest n with s_pref[n] * Hkv <= f0 (that sequence is not empty)
-    int n;
+    RowCursor first;
     {
         int lo = 0, hi = nseq;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (uniform(s_pref[mid]) * Hkv <= f0) lo = mid; else hi = mid;
         }
-        n = lo;
+        first.n = lo;
+        first.pref = uniform(s_pref[lo]);
+        first.tiles = uniform(s_pref[lo + 1]) - first.pref;
+        first.kvh = (f0 - first.pref * Hkv) / first.tiles;
     }
-    int pref_n = uniform(s_pref[n]);
-    int t_n = uniform(s_pref[n + 1]) - pref_n;
-    int kvh = (f0 - pref_n * Hkv) / t_n;
-    int tile = (f0 - pref_n * Hkv) - kvh * t_n;
+    const int first_tile = (f0 - first.pref * Hkv) - first.kvh * first.tiles;
 
-    const size_t head_elems = size_t(p.block_size) * D;
-    const size_t block_elems = head_elems * Hkv;
-    const int sub_mask = (1 << tiles_per_block_log2) - 1;
+    // ---- issue cursor: one tile ahead of the compute cursor
+    RowCursor ri = first;
+    int ti = first_tile;             // next tile of row ri to load
+    int chunk_i = first_tile;        // blk_cur holds the ids of tiles [chunk_i, chunk_i + 64)
+    int blk_cur = load_blocks(ri, chunk_i);
+    int blk_next_row = load_blocks(next_row(ri), 0);
 
-    int f = f0;
-    while (f < f1) {
-        // ---- one segment: tiles [ta, tb) of row (n, kvh)
-        const int ta = tile;
-        const int tb = min(t_n, ta + (f1 - f));
-        const int ctx = uniform(context_lens[n]);
-        const int row_f = pref_n * Hkv + kvh * t_n;          // flat index of the row's tile 0
-        const int j0 = row_f / C;
-        const int cnt = (row_f + t_n - 1) / C - j0 + 1;      // workers that touch this row
-        const int slot = worker - j0;                        // my partial index within the row
-        const int32_t *table = block_tables + size_t(n) * p.max_blocks_per_seq;
-        const size_t head_off = size_t(kvh) * head_elems;
-
-        bf16x8 qb[4];
-        load_q_operand(qb, q + (size_t(n) * p.num_q_heads + kvh * G + (r < G ? r : 0)) * D, quad, r < G);
-        HeadState st;
-        st.reset();
-
-        for (int c0 = ta; c0 < tb; c0 += 64) {
-            const int nt = min(64, tb - c0);
-            int my_blk = 0;  // physical block of tile c0 + lane
-            if (lane < nt) my_blk = table[(c0 + lane) >> tiles_per_block_log2];
-
-            auto issue = [&](uint4(&kr)[4], uint4(&vr)[4], int it) __attribute__((always_inline)) {
-                const int blk = __builtin_amdgcn_readlane(my_blk, it);
-                const size_t base = size_t(blk) * block_elems + head_off + size_t((c0 + it) & sub_mask) * kTileElems;
-                issue_tile_direct(kr, vr, k_cache + base, v_cache + base, quad, r);
-            };
-            auto compute = [&](uint4(&kr)[4], uint4(&vr)[4], int it) __attribute__((always_inline)) {
-                bf16x8 ka[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
-                compute_tile(st, ka, vr, qb, p.scale_log2e, ctx - (c0 + it) * kTileTokens, quad);
-            };
-
-            uint4 kA[4], vA[4], kB[4], vB[4];
-            issue(kA, vA, 0);
-            for (int it = 0; it < nt; it += 2) {
-                const bool has1 = it + 1 < nt;
-                if (has1) issue(kB, vB, it + 1);
-                compute(kA, vA, it);
-                if (has1) {
-                    if (it + 2 < nt) issue(kA, vA, it + 2);
-                    compute(kB, vB, it + 1);
-                }
-            }
+    auto issue_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
+        if (ti == ri.tiles) {  // the row is exhausted: move to the next one (ids already here)
+            ri = next_row(ri);
+            ti = 0;
+            chunk_i = 0;
+            blk_cur = blk_next_row;
+            blk_next_row = load_blocks(next_row(ri), 0);
+        } else if (ti - chunk_i == 64) {  // long row: fetch the next 64 block ids
+            chunk_i += 64;
+            blk_cur = load_blocks(ri, chunk_i);
         }
-        st.finish();
+        const int blk = __builtin_amdgcn_readlane(blk_cur, ti - chunk_i);
+        const size_t base = size_t(blk) * block_elems + size_t(ri.kvh) * head_elems +
+                            size_t(ti & sub_mask) * kTileElems;
+        issue_tile_direct(kr, vr, k_cache + base, v_cache + base, quad, r);
+        ++ti;
+    };
 
-        // ---- write the segment: lane (quad, r < G) holds O[head r][32*quad .. +31]
-        if (r < G) {
-            const size_t orow = size_t(n) * p.num_q_heads + kvh * G + r;
+    // ---- compute cursor
+    RowCursor rc = first;
+    int tc = first_tile;             // next tile of row rc to consume
+    int seg_first = first_tile;      // first tile of the current segment
+    int ctx_c = uniform(s_ctx[rc.n]);
+    bf16x8 qb[4], qb_next[4];
+    load_q(qb, rc);
+    load_q(qb_next, next_row(rc));
+    HeadState st;
+    st.reset();
+
+    // Write the finished segment [seg_first, tc) of row rc.
+    auto finalize = [&]() __attribute__((always_inline)) {
+        st.finish();
+        const int row_f = rc.pref * Hkv + rc.kvh * rc.tiles;  // flat index of the row's tile 0
+        const int j0 = row_f / C;
+        const int cnt = (row_f + rc.tiles - 1) / C - j0 + 1;  // workers that touch this row
+        const int slot = worker - j0;                         // my partial index within the row
+        if (r < G) {  // lane (quad, r) holds O[head r][32*quad .. +31]
+            const size_t orow = size_t(rc.n) * p.num_q_heads + rc.kvh * G + r;
             if (cnt == 1) {
                 const float inv = 1.0f / st.l;
                 uint16_t *dst = out + orow * D + 32 * quad;
@@ -183,20 +232,48 @@ __global__ __launch_bounds__(kThreads, 3) void pa_stream_mfma_kernel(
                 if (quad == 0) *reinterpret_cast<float2 *>(ws.ml + ps * 2) = float2{st.m, st.l};
             }
         }
-        if (ta == 0 && lane == 0) ws.cnt[n * Hkv + kvh] = cnt;
+        if (seg_first == 0 && lane == 0) ws.cnt[rc.n * Hkv + rc.kvh] = cnt;
+    };
 
-        // ---- advance to the next row
-        f += tb - ta;
-        tile = 0;
-        if (tb == t_n && f < f1) {
-            if (++kvh == Hkv) {
-                kvh = 0;
-                do { ++n; } while (n < nseq - 1 && uniform(s_pref[n + 1]) == uniform(s_pref[n]));
-                pref_n = uniform(s_pref[n]);
-                t_n = uniform(s_pref[n + 1]) - pref_n;
-            }
+    auto compute_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
+        if (tc == rc.tiles) {  // the tile to consume opens a new row
+            finalize();
+            rc = next_row(rc);
+            tc = 0;
+            seg_first = 0;
+            ctx_c = uniform(s_ctx[rc.n]);
+            st.reset();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) qb[j] = qb_next[j];
+            load_q(qb_next, next_row(rc));
         }
+        bf16x8 ka[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
+        compute_tile(st, ka, vr, qb, p.scale_log2e, ctx_c - tc * kTileTokens, quad);
+        ++tc;
+    };
+
+    // Two register sets; the steady-state loop has no branch around the tile loads, so the
+    // compiler's wait counts let the newest 8 loads stay in flight while the older tile is
+    // consumed.  The 1- or 2-tile tail is peeled.
+    uint4 kA[4], vA[4], kB[4], vB[4];
+    issue_next(kA, vA);
+    int it = 0;
+    for (; it + 2 < NT; it += 2) {
+        issue_next(kB, vB);
+        compute_next(kA, vA);
+        issue_next(kA, vA);
+        compute_next(kB, vB);
     }
+    if (it + 1 < NT) {
+        issue_next(kB, vB);
+        compute_next(kA, vA);
+        compute_next(kB, vB);
+    } else {
+        compute_next(kA, vA);
+    }
+    finalize();
 }
 
 }  // namespace
