@@ -215,17 +215,15 @@ def main() -> int:
         import oracle
         threads = args.cpu_threads or min(oracle.num_threads_available(), os.cpu_count() or 1)
         h2 = np.zeros((2, pool2_blocks) + pool_np.shape[2:], dtype=np.uint16)
-        budget, done_rows, t_cpu = 20.0, 0, 0.0
-        rows_all = [(n, h) for n in range(w.num_seqs) for h in range(w.num_q_heads)]
-        # whole batches while they fit the budget; always at least one full batch
-        passes = 0
+        # bounded sample: whole steps of the same batch, repeated until ~10 s of CPU time
+        t_cpu, passes = 0.0, 0
         while True:
             t = time.perf_counter()
             oracle.attention_of_workload(w, num_threads=threads)
             oracle.kv_block_copy(pool_np, h2, mapping_np)
             t_cpu += time.perf_counter() - t
             passes += 1
-            if t_cpu + t_cpu / passes > budget or passes >= 8:
+            if t_cpu >= 10.0 or t_cpu + t_cpu / passes > 30.0:
                 break
         cpu_s = t_cpu / passes
         cpu = {"value": round(step_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(threads),

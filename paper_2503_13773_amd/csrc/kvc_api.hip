@@ -86,11 +86,7 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
         pl->partition_tokens = min_chunk * 16;
         pl->min_chunk_tiles = min_chunk;
         pl->max_partitions = int(parts);
-#ifdef KVC_PROBE_WGS_PER_CU
-        pl->partial_grid = kvc::kNumCUs * KVC_PROBE_WGS_PER_CU;
-#else
         pl->partial_grid = kvc::kNumCUs;  // 4 wavefronts per CU: one worker per SIMD
-#endif
         pl->merge_grid = ceil_div(rows, kvc::kWaves);
         pl->max_context_len = max_ctx;
         const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);

@@ -88,11 +88,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // 16-byte load of KV data.  K and V are streamed once per step, so the load carries the
 // non-temporal hint (no reuse expected in L2 / the memory-side cache).
 __device__ inline uint4 load16_stream(const uint16_t *p) {
-#ifdef KVC_PROBE_PLAIN_LOADS
-    return *reinterpret_cast<const uint4 *>(p);
-#else
     return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
-#endif
 }
 
 // Issue the 8 x 16-byte loads of one tile: K straight into the A-operand layout (16 rows x
@@ -100,11 +96,7 @@ __device__ inline uint4 load16_stream(const uint16_t *p) {
 __device__ inline void issue_tile_direct(uint4 (&kr)[4], uint4 (&vr)[4], const uint16_t *kp,
                                          const uint16_t *vp, int quad, int r) {
 #pragma unroll
-#ifdef KVC_PROBE_COALESCED_K  /* timing probe only: wrong numerics */
-    for (int j = 0; j < 4; ++j) kr[j] = load16_stream(kp + (4 * quad + j) * D + 8 * r);
-#else
     for (int j = 0; j < 4; ++j) kr[j] = load16_stream(kp + r * D + 32 * j + 8 * quad);
-#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i) vr[i] = load16_stream(vp + (4 * quad + i) * D + 8 * r);
 }
@@ -113,15 +105,6 @@ __device__ inline void issue_tile_direct(uint4 (&kr)[4], uint4 (&vr)[4], const u
 // that lie inside the context (16 for a full tile, wavefront-uniform).
 __device__ inline void compute_tile(HeadState &st, const bf16x8 (&ka)[4], uint4 (&vr)[4],
                                     const bf16x8 (&qb)[4], float scale_log2e, int valid, int quad) {
-#ifdef KVC_PROBE_NO_COMPUTE  /* timing probe only: wrong numerics */
-    for (int j = 0; j < 4; ++j) {
-        const uint4 kk = __builtin_bit_cast(uint4, ka[j]);
-        st.acc[j][0] += __uint_as_float((kk.x ^ kk.y ^ kk.z ^ kk.w) & 0x3fffffffu);
-        st.acc[j + 4][0] += __uint_as_float((vr[j].x ^ vr[j].y ^ vr[j].z ^ vr[j].w) & 0x3fffffffu);
-    }
-    st.m = 0.f; st.l = 1.f;
-    return;
-#endif
     floatx4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j], qb[j], s, 0, 0, 0);

@@ -88,14 +88,14 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
         const size_t base = size_t(blk) * block_elems + kvh * head_elems + size_t(gt & sub_mask) * kTileElems;
         const uint16_t *kp = k_cache + base;
         const uint16_t *vp = v_cache + base;
+        if (KLDS) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (KLDS) kr[i] = *reinterpret_cast<const uint4 *>(kp + i * 512 + lane * 8);
-            else      kr[i] = *reinterpret_cast<const uint4 *>(kp + r * D + 32 * i + 8 * quad);
+            for (int i = 0; i < 4; ++i) kr[i] = load16_stream(kp + i * 512 + lane * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vr[i] = load16_stream(vp + (4 * quad + i) * D + 8 * r);
+        } else {
+            issue_tile_direct(kr, vr, kp, vp, quad, r);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            vr[i] = *reinterpret_cast<const uint4 *>(vp + (4 * quad + i) * D + 8 * r);
     };
 
     auto compute = [&](uint4(&kr)[4], uint4(&vr)[4], int it) __attribute__((always_inline)) {

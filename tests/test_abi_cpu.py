@@ -1,0 +1,176 @@
+"""The C ABI without a GPU: the library loads, exports every symbol include/kvc.h declares,
+struct layouts match a C compiler's, and host-visible argument errors come back as status
+codes before anything is launched."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvc.h")
+
+
+@pytest.fixture(scope="module")
+def K():
+    import paper_2503_13773_amd as K
+    if not os.path.exists(K.library_path()):
+        from paper_2503_13773_amd.build import build_library
+        build_library()
+    K.lib()
+    return K
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"KVC_API\s+[\w\s\*]+?\b(kvc_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("kvc_paged_attention_decode", "kvc_kv_block_copy", "kvc_attn_plan",
+                 "kvc_paged_attention_decode_workspace_bytes", "kvc_paged_attention_decode_partial",
+                 "kvc_paged_attention_decode_merge", "kvc_validate_attention_inputs",
+                 "kvc_validate_block_mapping", "kvc_status_string", "kvc_version",
+                 "kvc_last_hip_error"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(K):
+    lib = ctypes.CDLL(K.library_path())
+    for name in declared_functions():
+        assert getattr(lib, name) is not None, name
+    out = subprocess.run(["nm", "-D", "--defined-only", K.library_path()], capture_output=True, text=True).stdout
+    exported = set(re.findall(r"\bT\s+(kvc_\w+)", out))
+    assert set(declared_functions()) <= exported
+    assert K.version() >= 100
+
+
+def test_header_is_plain_c_and_struct_layouts_match_ctypes(K, tmp_path):
+    src = tmp_path / "layout.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "kvc.h"
+int main(void) {
+  printf("%zu %zu %zu\n", sizeof(kvc_attn_desc), sizeof(kvc_attn_plan_info), sizeof(kvc_pool));
+  printf("%zu %zu %zu\n", offsetof(kvc_attn_desc, kernel), offsetof(kvc_attn_plan_info, workspace_bytes),
+         offsetof(kvc_pool, num_planes));
+  return 0;
+}''')
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe)])
+    a, b = subprocess.run([str(exe)], capture_output=True, text=True).stdout.split("\n")[:2]
+    assert [int(x) for x in a.split()] == [ctypes.sizeof(K.AttnDesc), ctypes.sizeof(K.AttnPlan),
+                                           ctypes.sizeof(K.Pool)]
+    assert [int(x) for x in b.split()] == [K.AttnDesc.kernel.offset, K.AttnPlan.workspace_bytes.offset,
+                                           K.Pool.num_planes.offset]
+    subprocess.check_call(["g++", "-std=c++17", "-fsyntax-only", "-x", "c++", "-I",
+                           os.path.join(ROOT, "include"), HEADER])
+
+
+def desc(K, **kw):
+    d = dict(num_seqs=64, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16,
+             max_blocks_per_seq=256, num_pool_blocks=4096, dtype=K.KVC_BF16, max_context_len=0,
+             partition_tokens=0, kernel=0, reserved=0)
+    d.update(kw)
+    return K.AttnDesc(**d)
+
+
+def plan_status(K, d):
+    plan = K.AttnPlan()
+    return K.lib().kvc_attn_plan(ctypes.byref(d), ctypes.byref(plan)), plan
+
+
+def test_plan_picks_kernels_and_sizes_workspace(K):
+    rc, p = plan_status(K, desc(K))
+    assert rc == 0 and p.kernel == K.KERNEL_MFMA_BALANCED and p.partial_grid == 256 and p.merge_grid == 512
+    assert p.max_partitions == 33 and p.workspace_bytes == K.workspace_bytes(desc(K)) > 0
+    rc, p = plan_status(K, desc(K, dtype=K.KVC_F32, head_dim=64, num_q_heads=8, num_kv_heads=8,
+                                max_blocks_per_seq=16))
+    assert rc == 0 and p.kernel == K.KERNEL_VALU and p.max_partitions == 1 and p.workspace_bytes == 0
+    rc, p = plan_status(K, desc(K, block_size=8))
+    assert rc == 0 and p.kernel == K.KERNEL_VALU
+    rc, p = plan_status(K, desc(K, num_seqs=2000))          # too many sequences for the balanced kernel
+    assert rc == 0 and p.kernel == K.KERNEL_MFMA
+    rc, p = plan_status(K, desc(K, kernel=K.KERNEL_MFMA, partition_tokens=512))
+    assert rc == 0 and p.partition_tokens == 512 and p.max_partitions == 8 and p.partial_grid == 64 * 8 * 8
+    rc, p = plan_status(K, desc(K, kernel=K.KERNEL_VALU, max_context_len=1000))
+    assert rc == 0 and p.max_partitions == 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(num_q_heads=30), -2), (dict(num_kv_heads=0), -2), (dict(head_dim=0), -2),
+    (dict(head_dim=96), -4), (dict(block_size=24), -4), (dict(block_size=512), -4),
+    (dict(dtype=7), -3), (dict(max_context_len=4097), -2), (dict(max_context_len=-1), -2),
+    (dict(partition_tokens=100), -2), (dict(partition_tokens=8192), -2), (dict(kernel=9), -2),
+    (dict(reserved=1), -2), (dict(num_seqs=-1), -2), (dict(max_blocks_per_seq=0), -2),
+    (dict(kernel=2, dtype=0), -4), (dict(kernel=2, num_q_heads=32, num_kv_heads=1), -4),
+    (dict(kernel=4, num_seqs=1025), -4), (dict(kernel=3, block_size=8), -4),
+])
+def test_bad_descriptors_are_rejected(K, kw, status):
+    rc, _ = plan_status(K, desc(K, **kw))
+    assert rc == status, K.status_string(rc)
+    assert K.workspace_bytes(desc(K, **kw)) == 0
+
+
+def test_attention_argument_errors_come_back_before_any_launch(K):
+    L = K.lib()
+    d = desc(K)
+    good = 0x10000  # never dereferenced: every call below fails validation first
+    args = lambda **o: [o.get("q", good), o.get("k", good), o.get("v", good), o.get("bt", good),
+                        o.get("cl", good), o.get("scale", 0.088), o.get("out", good), ctypes.byref(d),
+                        o.get("ws", good), o.get("wsb", 1 << 30), None]
+    assert L.kvc_paged_attention_decode(*args(q=None)) == -1
+    assert L.kvc_paged_attention_decode(*args(bt=None)) == -1
+    assert L.kvc_paged_attention_decode(*args(out=None)) == -1
+    assert L.kvc_paged_attention_decode(*args(k=good + 8)) == -6
+    assert L.kvc_paged_attention_decode(*args(scale=float("nan"))) == -2
+    assert L.kvc_paged_attention_decode(*args(ws=None)) == -5
+    assert L.kvc_paged_attention_decode(*args(wsb=1024)) == -5
+    assert L.kvc_paged_attention_decode(*args(ws=good + 64)) == -6
+    assert L.kvc_paged_attention_decode_partial(*args(v=None)) == -1
+    assert L.kvc_paged_attention_decode_merge(None, good, ctypes.byref(d), good, 1 << 30, None) == -1
+    assert L.kvc_paged_attention_decode(good, good, good, good, good, 0.1, good, None, good, 0, None) == -1
+    # an empty batch is a no-op that needs no pointers at all
+    d0 = desc(K, num_seqs=0)
+    assert L.kvc_paged_attention_decode(None, None, None, None, None, 0.1, None, ctypes.byref(d0), None, 0, None) == 0
+    assert "workspace" in K.status_string(-5) and K.status_string(0) == "ok"
+
+
+def test_block_copy_argument_errors(K):
+    L = K.lib()
+    pool = lambda **o: K.Pool(base=o.get("base", 0x10000), num_blocks=o.get("nb", 100),
+                              block_bytes=o.get("bb", 32768), plane_stride_bytes=o.get("ps", 100 * 32768),
+                              num_planes=o.get("np", 2), reserved=o.get("rsv", 0))
+    call = lambda s, d, m=0x20000, n=4: L.kvc_kv_block_copy(ctypes.byref(s), ctypes.byref(d), m, n, None)
+    assert call(pool(), pool(bb=16384)) == -2            # block sizes differ
+    assert call(pool(), pool(np=1)) == -2                # plane counts differ
+    assert call(pool(bb=100), pool(bb=100)) == -6        # not a multiple of 16
+    assert call(pool(base=0x10008), pool()) == -6
+    assert call(pool(ps=32768 * 99), pool()) == -2       # planes would overlap
+    assert call(pool(ps=32768 * 100 + 8), pool()) == -6
+    assert call(pool(nb=0), pool()) == -2
+    assert call(pool(rsv=3), pool()) == -2
+    assert call(pool(base=None), pool()) == -1
+    assert call(pool(), pool(), m=None) == -1
+    assert call(pool(), pool(), n=-1) == -2
+    assert call(pool(np=70000, ps=32768 * 100), pool(np=70000, ps=32768 * 100)) == -4
+    assert L.kvc_kv_block_copy(None, ctypes.byref(pool()), 0x20000, 1, None) == -1
+    assert call(pool(base=None), pool(base=None), m=None, n=0) == 0   # nothing to do
+
+
+def test_binding_refuses_host_tensors(K):
+    import torch
+    q = torch.zeros(2, 8, 128, dtype=torch.bfloat16)
+    kc = torch.zeros(4, 2, 16, 128, dtype=torch.bfloat16)
+    bt = torch.zeros(2, 4, dtype=torch.int32)
+    cl = torch.ones(2, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        K.paged_attention_decode(q, kc, kc, bt, cl, 0.1)
+    with pytest.raises((ValueError, TypeError)):
+        K.kv_block_copy(kc[None], kc[None], torch.zeros(1, 2, dtype=torch.int64))
