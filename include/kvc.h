@@ -85,9 +85,10 @@ typedef struct {
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 means
                                    max_blocks_per_seq * block_size.  A tight bound keeps
                                    the launch grid and the workspace small. */
-    int32_t partition_tokens;   /* split-K partition length in tokens (multiple of 16); 0 lets the
-                                   library choose.  For KVC_KERNEL_MFMA_BALANCED: the smallest
-                                   range a wavefront takes. */
+    int32_t partition_tokens;   /* split-K partition length in tokens (multiple of 16, at most
+                                   4096); 0 lets the library choose.  With kernel ==
+                                   KVC_KERNEL_MFMA_BALANCED: the smallest range a wavefront takes
+                                   (multiple of 16, at most 2^20). */
     int32_t kernel;             /* kvc_kernel */
     int32_t reserved;           /* must be 0 */
 } kvc_attn_desc;

@@ -22,6 +22,7 @@ int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 constexpr int kMaxPartitionTokens = 4096;  // 4 wavefronts x 64 table entries x 16 tokens
+constexpr int kMaxBalancedChunkTokens = 1 << 20;  // explicit minimum range of the balanced kernel
 constexpr int64_t kMaxGrid = 0x7fffffff;
 
 struct Plan {
@@ -45,7 +46,8 @@ bool mfma_ok(const kvc_attn_desc &d) {
 // The balanced kernel keeps a prefix sum over the batch in LDS and indexes flat tiles in int32.
 bool balanced_ok(const kvc_attn_desc &d, int max_ctx) {
     return mfma_ok(d) && d.num_seqs <= kvc::kMaxStreamSeqs &&
-           int64_t(d.num_seqs) * d.num_kv_heads * ceil_div(max_ctx, 16) < (int64_t(1) << 30);
+           int64_t(d.num_seqs) * d.num_kv_heads * ceil_div(max_ctx, 16) < (int64_t(1) << 30) &&
+           int64_t(d.num_pool_blocks) * d.num_kv_heads * (d.block_size / 16) < (int64_t(1) << 31);
 }
 
 int make_plan(const kvc_attn_desc *d, Plan *pl) {
@@ -62,7 +64,8 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
     if (table_tokens > 0x40000000) return KVC_ERR_BAD_SHAPE;
     if (d->max_context_len > table_tokens) return KVC_ERR_BAD_SHAPE;
     const int max_ctx = d->max_context_len ? d->max_context_len : int(table_tokens);
-    if (d->partition_tokens % 16 != 0 || d->partition_tokens > kMaxPartitionTokens)
+    if (d->partition_tokens % 16 != 0) return KVC_ERR_BAD_SHAPE;
+    if (d->partition_tokens > (d->kernel == KVC_KERNEL_MFMA_BALANCED ? kMaxBalancedChunkTokens : kMaxPartitionTokens))
         return KVC_ERR_BAD_SHAPE;
 
     int kernel = d->kernel;

@@ -47,6 +47,8 @@ using namespace mfma;
 
 __device__ inline int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+constexpr int kStageTiles = 256;  // tile addresses staged in LDS per wavefront at a time
+
 // A row of the flattened work: (sequence, KV head); all fields wavefront-uniform.
 struct RowCursor {
     int n;       // sequence
@@ -63,6 +65,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of tiles per sequence (+ guard)
     __shared__ int s_ctx[kMaxStreamSeqs];       // context length per sequence
     __shared__ int s_wave_tot[kWaves];
+    __shared__ int s_tile[kWaves][kStageTiles];  // per worker: (physical 4 KiB tile index) of its next tiles
 
     const int tid = threadIdx.x;
     const int wave = uniform(tid >> 6), lane = tid & 63;
@@ -118,8 +121,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const int f0 = worker * C;
     const int NT = min(T, f0 + C) - f0;  // tiles of this worker, >= 1
 
-    const size_t head_elems = size_t(p.block_size) * D;
-    const size_t block_elems = head_elems * Hkv;
     const int sub_mask = (1 << tiles_per_block_log2) - 1;
 
     // Row after `c` in flat order, skipping empty sequences.  Past the last row it parks on
@@ -134,14 +135,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             o.tiles = uniform(s_pref[o.n + 1]) - o.pref;
         }
         return o;
-    };
-    // Block ids of tiles [first, first + 64) of a row, one per lane (entries past the row's
-    // last tile are not read).
-    auto load_blocks = [&](const RowCursor &c, int first) __attribute__((always_inline)) {
-        int b = 0;
-        if (c.n < nseq && first + lane < c.tiles)
-            b = block_tables[size_t(c.n) * p.max_blocks_per_seq + ((first + lane) >> tiles_per_block_log2)];
-        return b;
     };
     auto load_q = [&](bf16x8(&qb)[4], const RowCursor &c) __attribute__((always_inline)) {
         const bool active = r < G && c.n < nseq;
@@ -164,29 +157,44 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     }
     const int first_tile = (f0 - first.pref * Hkv) - first.kvh * first.tiles;
 
-    // ---- issue cursor: one tile ahead of the compute cursor
-    RowCursor ri = first;
-    int ti = first_tile;             // next tile of row ri to load
-    int chunk_i = first_tile;        // blk_cur holds the ids of tiles [chunk_i, chunk_i + 64)
-    int blk_cur = load_blocks(ri, chunk_i);
-    int blk_next_row = load_blocks(next_row(ri), 0);
-
-    auto issue_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
-        if (ti == ri.tiles) {  // the row is exhausted: move to the next one (ids already here)
-            ri = next_row(ri);
-            ti = 0;
-            chunk_i = 0;
-            blk_cur = blk_next_row;
-            blk_next_row = load_blocks(next_row(ri), 0);
-        } else if (ti - chunk_i == 64) {  // long row: fetch the next 64 block ids
-            chunk_i += 64;
-            blk_cur = load_blocks(ri, chunk_i);
+    // ---- tile addresses of the worker's range, staged in LDS
+    // Entry k holds the index, in 4 KiB tiles, of the worker's k-th tile inside the KV pools:
+    // (block * Hkv + kv head) * tiles_per_block + tile-in-block.  Staging them up front keeps the
+    // steady-state loop free of dependent block-table loads: the issue side of the pipeline
+    // needs one LDS read per tile and no row bookkeeping at all.
+    const int tiles_per_block = 1 << tiles_per_block_log2;
+    RowCursor rf = first;           // fill cursor
+    int tf = first_tile;            // next tile of row rf to stage
+    int staged_base = 0;            // worker-relative index of s_tile[wave][0]
+    auto stage_tiles = [&](int from) __attribute__((always_inline)) {
+        const int count = min(kStageTiles, NT - from);
+        int off = 0;
+        while (off < count) {
+            if (tf == rf.tiles) {
+                rf = next_row(rf);
+                tf = 0;
+            }
+            if (rf.n >= nseq) break;  // cannot happen for a consistent batch; never walk past the last row
+            const int seg = min(rf.tiles - tf, count - off);  // >= 1
+            const int32_t *table = block_tables + size_t(rf.n) * p.max_blocks_per_seq;
+            for (int j = lane; j < seg; j += 64) {
+                const int t = tf + j;
+                const int blk = table[t >> tiles_per_block_log2];
+                s_tile[wave][off + j] = (blk * Hkv + rf.kvh) * tiles_per_block + (t & sub_mask);
+            }
+            off += seg;
+            tf += seg;
         }
-        const int blk = __builtin_amdgcn_readlane(blk_cur, ti - chunk_i);
-        const size_t base = size_t(blk) * block_elems + size_t(ri.kvh) * head_elems +
-                            size_t(ti & sub_mask) * kTileElems;
+        staged_base = from;
+    };
+    stage_tiles(0);
+
+    int ki = 0;  // worker-relative index of the next tile to load
+    auto issue_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
+        if (ki - staged_base == kStageTiles) stage_tiles(ki);  // very long ranges only
+        const size_t base = size_t(uniform(s_tile[wave][ki - staged_base])) * kTileElems;
         issue_tile_direct(kr, vr, k_cache + base, v_cache + base, quad, r);
-        ++ti;
+        ++ki;
     };
 
     // ---- compute cursor
@@ -235,8 +243,16 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         if (seg_first == 0 && lane == 0) ws.cnt[rc.n * Hkv + rc.kvh] = cnt;
     };
 
-    auto compute_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
-        if (tc == rc.tiles) {  // the tile to consume opens a new row
+    // Consumes the tile under the compute cursor.  When it was the last tile of the row the
+    // segment is written and the state switches to the next row at once: the stores and the
+    // Q prefetch are then issued as early as possible before the next wait on tile data.
+    auto compute_next = [&](uint4(&kr)[4], uint4(&vr)[4], bool more) __attribute__((always_inline)) {
+        bf16x8 ka[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
+        compute_tile(st, ka, vr, qb, p.scale_log2e, ctx_c - tc * kTileTokens, quad);
+        ++tc;
+        if (tc == rc.tiles && more) {  // row finished and the worker has more tiles
             finalize();
             rc = next_row(rc);
             tc = 0;
@@ -247,11 +263,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             for (int j = 0; j < 4; ++j) qb[j] = qb_next[j];
             load_q(qb_next, next_row(rc));
         }
-        bf16x8 ka[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
-        compute_tile(st, ka, vr, qb, p.scale_log2e, ctx_c - tc * kTileTokens, quad);
-        ++tc;
     };
 
     // Two register sets; the steady-state loop has no branch around the tile loads, so the
@@ -262,16 +273,16 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     int it = 0;
     for (; it + 2 < NT; it += 2) {
         issue_next(kB, vB);
-        compute_next(kA, vA);
+        compute_next(kA, vA, true);
         issue_next(kA, vA);
-        compute_next(kB, vB);
+        compute_next(kB, vB, true);
     }
     if (it + 1 < NT) {
         issue_next(kB, vB);
-        compute_next(kA, vA);
-        compute_next(kB, vB);
+        compute_next(kA, vA, true);
+        compute_next(kB, vB, false);
     } else {
-        compute_next(kA, vA);
+        compute_next(kA, vA, false);
     }
     finalize();
 }

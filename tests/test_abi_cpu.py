@@ -107,7 +107,8 @@ def test_plan_picks_kernels_and_sizes_workspace(K):
     (dict(num_q_heads=30), -2), (dict(num_kv_heads=0), -2), (dict(head_dim=0), -2),
     (dict(head_dim=96), -4), (dict(block_size=24), -4), (dict(block_size=512), -4),
     (dict(dtype=7), -3), (dict(max_context_len=4097), -2), (dict(max_context_len=-1), -2),
-    (dict(partition_tokens=100), -2), (dict(partition_tokens=8192), -2), (dict(kernel=9), -2),
+    (dict(partition_tokens=100), -2), (dict(partition_tokens=8192, kernel=2), -2),
+    (dict(partition_tokens=(1 << 20) + 16, kernel=4), -2), (dict(kernel=9), -2),
     (dict(reserved=1), -2), (dict(num_seqs=-1), -2), (dict(max_blocks_per_seq=0), -2),
     (dict(kernel=2, dtype=0), -4), (dict(kernel=2, num_q_heads=32, num_kv_heads=1), -4),
     (dict(kernel=4, num_seqs=1025), -4), (dict(kernel=3, block_size=8), -4),

@@ -152,6 +152,15 @@ def test_maximum_partition_length(oracle_mod, kernel):
     check(w, oracle_mod, "pt=4096", kernel=kernel, partition_tokens=4096)
 
 
+def test_balanced_ranges_longer_than_the_staging_window(oracle_mod):
+    """A worker range of 512 tiles makes the balanced kernel refill its LDS window of tile
+    addresses (256 entries) mid-range, also across a row change."""
+    w = custom(140, dtype=W.BF16, lens=[20000, 37, 9000], hq=2, hkv=1, d=128, bs=16)
+    check(w, oracle_mod, "balanced chunk=8192", kernel=BALANCED, partition_tokens=8192)
+    w2 = custom(141, dtype=W.BF16, lens=[6000, 6000], hq=8, hkv=2, d=128, bs=32)
+    check(w2, oracle_mod, "balanced chunk=4800", kernel=BALANCED, partition_tokens=4800)
+
+
 @pytest.mark.parametrize("dtype,kernels", [(W.F32, [VALU]), (W.BF16, [VALU, MFMA, MFMA_LDS, BALANCED])])
 def test_context_one_returns_v_bit_exactly(dtype, kernels):
     d_ = 64 if dtype == W.F32 else 128
