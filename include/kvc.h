@@ -158,6 +158,22 @@ KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int
                                   const kvc_attn_desc *desc, void *hip_stream);
 
 /*
+ * Write one new token per sequence into the block-allocated cache (the step that precedes
+ * the decode attention of an iteration: every running request produces one token whose K and V
+ * land in the next free slot of its last block; Section 1, Section 3.3).
+ *   k_new, v_new   T [num_seqs][num_kv_heads][head_dim]   (device, 16-byte aligned)
+ *   positions      int32 [num_seqs] (device): token index to write for each sequence; the
+ *                  token goes to block block_tables[n][pos / block_size], slot pos % block_size.
+ *                  A negative position skips the sequence.
+ * Every other byte of the caches is left untouched.  Uses desc->num_seqs, num_kv_heads,
+ * head_dim, block_size, max_blocks_per_seq and dtype (the attention-only fields are ignored
+ * but must be valid).  Positions and block ids are not range-checked.
+ */
+KVC_API int kvc_kv_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                const int32_t *block_tables, const int32_t *positions,
+                                const kvc_attn_desc *desc, void *hip_stream);
+
+/*
  * A KV pool as the copy sees it: num_planes planes (K or V of one layer each) of num_blocks
  * blocks of block_bytes bytes; plane p starts at base + p * plane_stride_bytes.
  */

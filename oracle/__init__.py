@@ -48,6 +48,11 @@ def _load():
         lib.oracle_kv_block_copy.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64]
+        lib.oracle_kv_cache_append.restype = ctypes.c_int
+        lib.oracle_kv_cache_append.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64]
         lib.oracle_num_threads_available.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -129,3 +134,28 @@ def kv_block_copy(src_pool: np.ndarray, dst_pool: np.ndarray, block_mapping: np.
                                   mapping.ctypes.data, mapping.shape[0])
     if rc != 0:
         raise ValueError("block id outside the pool")
+
+
+def kv_cache_append(k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+                    block_tables: np.ndarray, positions: np.ndarray) -> None:
+    """cache[table[n][pos // Bs]][h][pos % Bs] = new[n][h] for K and V, in place, bytewise.
+
+    k_new, v_new [num_seqs][Hkv][D]; caches [NB][Hkv][Bs][D] (same dtype); positions int32
+    [num_seqs], negative = skip.
+    """
+    lib = _load()
+    for a in (k_new, v_new, k_cache, v_cache):
+        assert a.flags.c_contiguous
+    assert k_cache.flags.writeable and v_cache.flags.writeable
+    nseq, hkv, d = k_new.shape
+    nb, hkv2, bs, d2 = k_cache.shape
+    assert (hkv2, d2) == (hkv, d) and v_new.shape == k_new.shape and v_cache.shape == k_cache.shape
+    assert k_new.dtype == k_cache.dtype == v_new.dtype == v_cache.dtype
+    block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+    positions = np.ascontiguousarray(positions, dtype=np.int32)
+    rc = lib.oracle_kv_cache_append(k_new.ctypes.data, v_new.ctypes.data, k_cache.ctypes.data,
+                                    v_cache.ctypes.data, block_tables.ctypes.data,
+                                    positions.ctypes.data, nseq, hkv, d * k_new.itemsize, bs,
+                                    block_tables.shape[1], nb)
+    if rc != 0:
+        raise ValueError("position or block id out of range")

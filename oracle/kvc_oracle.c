@@ -193,3 +193,40 @@ int oracle_kv_block_copy(const uint8_t *src, uint8_t *dst, int64_t block_bytes, 
                    src + p * src_plane_stride + mapping[2 * i] * block_bytes, (size_t)block_bytes);
     return 0;
 }
+
+/*
+ * Append one token per sequence (the cache write before each decode step; Section 1 and 3.1):
+ * for every sequence n with positions[n] >= 0 and every kv head h,
+ *   cache[block_tables[n][pos / Bs]][h][pos % Bs][:] = new[n][h][:]   (bytewise, K and V).
+ * row_bytes = head_dim * element size.  Returns -1 if a block id or position is out of range.
+ */
+int oracle_kv_cache_append(const uint8_t *k_new, const uint8_t *v_new, uint8_t *k_cache,
+                           uint8_t *v_cache, const int32_t *block_tables, const int32_t *positions,
+                           int num_seqs, int num_kv_heads, int64_t row_bytes, int block_size,
+                           int max_blocks_per_seq, int64_t num_pool_blocks)
+{
+    for (int n = 0; n < num_seqs; ++n) {
+        int pos = positions[n];
+        if (pos < 0)
+            continue;
+        if (pos / block_size >= max_blocks_per_seq)
+            return -1;
+        int64_t blk = block_tables[(int64_t)n * max_blocks_per_seq + pos / block_size];
+        if (blk < 0 || blk >= num_pool_blocks)
+            return -1;
+    }
+    for (int n = 0; n < num_seqs; ++n) {
+        int pos = positions[n];
+        if (pos < 0)
+            continue;
+        int64_t blk = block_tables[(int64_t)n * max_blocks_per_seq + pos / block_size];
+        int slot = pos % block_size;
+        for (int h = 0; h < num_kv_heads; ++h) {
+            int64_t dst = (((blk * num_kv_heads + h) * block_size) + slot) * row_bytes;
+            int64_t src = ((int64_t)n * num_kv_heads + h) * row_bytes;
+            memcpy(k_cache + dst, k_new + src, (size_t)row_bytes);
+            memcpy(v_cache + dst, v_new + src, (size_t)row_bytes);
+        }
+    }
+    return 0;
+}

@@ -74,6 +74,8 @@ def lib():
     L.kvc_paged_attention_decode_merge.argtypes = [i32p, vp, dp, vp, sz, vp]
     L.kvc_validate_attention_inputs.restype = ctypes.c_int
     L.kvc_validate_attention_inputs.argtypes = [i32p, i32p, dp, vp]
+    L.kvc_kv_cache_append.restype = ctypes.c_int
+    L.kvc_kv_cache_append.argtypes = [vp, vp, vp, vp, i32p, i32p, dp, vp]
     L.kvc_kv_block_copy.restype = ctypes.c_int
     L.kvc_kv_block_copy.argtypes = [pp, pp, vp, ctypes.c_int64, vp]
     L.kvc_validate_block_mapping.restype = ctypes.c_int
@@ -195,6 +197,27 @@ def validate_attention_inputs(block_tables, context_lens, desc: AttnDesc, stream
     """Blocking range check of the index arrays; returns the status (0 = fine)."""
     return int(lib().kvc_validate_attention_inputs(block_tables.data_ptr(), context_lens.data_ptr(),
                                                    ctypes.byref(desc), _stream_handle(stream)))
+
+
+def kv_cache_append(k_new, v_new, k_cache, v_cache, block_tables, positions, stream=None) -> None:
+    """Write token positions[n] of every sequence: cache[table[n][pos // Bs]][h][pos % Bs] = new[n][h]."""
+    for t in (k_new, v_new, k_cache, v_cache, block_tables, positions):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    nseq, hkv, d = k_new.shape
+    if v_new.shape != k_new.shape or k_cache.shape != v_cache.shape or k_cache.shape[1] != hkv \
+            or k_cache.shape[3] != d or not (k_new.dtype == v_new.dtype == k_cache.dtype == v_cache.dtype):
+        raise ValueError("k_new / v_new / caches do not match")
+    if block_tables.dtype != torch.int32 or positions.dtype != torch.int32 or positions.shape != (nseq,) \
+            or block_tables.shape[0] != nseq:
+        raise TypeError("block_tables / positions must be int32 and match the batch")
+    desc = AttnDesc(num_seqs=nseq, num_q_heads=hkv, num_kv_heads=hkv, head_dim=d,
+                    block_size=k_cache.shape[2], max_blocks_per_seq=block_tables.shape[1],
+                    num_pool_blocks=k_cache.shape[0], dtype=_dtype_code(k_new), max_context_len=0,
+                    partition_tokens=0, kernel=KERNEL_VALU, reserved=0)
+    _check(lib().kvc_kv_cache_append(k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
+                                     v_cache.data_ptr(), block_tables.data_ptr(), positions.data_ptr(),
+                                     ctypes.byref(desc), _stream_handle(stream)), "kvc_kv_cache_append")
 
 
 def pool_of(t: torch.Tensor) -> Pool:

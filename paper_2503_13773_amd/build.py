@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvc_hip.so")
-SOURCES = ["kvc_api.hip", "kv_block_copy.hip", "paged_attention_valu.hip",
+SOURCES = ["kvc_api.hip", "kv_block_copy.hip", "kv_cache_append.hip", "paged_attention_valu.hip",
            "paged_attention_mfma.hip", "paged_attention_mfma_stream.hip",
            "paged_attention_merge.hip"]
 # packed-fp32 instructions are switched off on purpose for this target

@@ -352,6 +352,23 @@ int kvc_validate_attention_inputs(const int32_t *block_tables, const int32_t *co
     return KVC_OK;
 }
 
+int kvc_kv_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                        const int32_t *block_tables, const int32_t *positions,
+                        const kvc_attn_desc *desc, void *hip_stream) {
+    Plan pl;
+    const int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (desc->num_seqs == 0) return KVC_OK;
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !positions) return KVC_ERR_NULL;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+        return KVC_ERR_ALIGN;
+    const int row_bytes = desc->head_dim * (desc->dtype == KVC_F32 ? 4 : 2);
+    const hipError_t e = kvc::launch_cache_append(
+        k_new, v_new, k_cache, v_cache, block_tables, positions, desc->num_seqs, desc->num_kv_heads,
+        row_bytes, ilog2(desc->block_size), desc->max_blocks_per_seq, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
 int kvc_kv_block_copy(const kvc_pool *src, const kvc_pool *dst, const int64_t *block_mapping,
                       int64_t num_pairs, void *hip_stream) {
     const int rc = check_pools(src, dst, block_mapping, num_pairs);

@@ -58,6 +58,10 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
                         int dtype, int head_dim, bool base2, bool counted, int grid,
                         hipStream_t stream);
+hipError_t launch_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                               const int32_t *block_tables, const int32_t *positions, int num_seqs,
+                               int num_kv_heads, int row_bytes, int block_size_log2,
+                               int max_blocks_per_seq, hipStream_t stream);
 hipError_t launch_block_copy(const kvc_pool &src, const kvc_pool &dst, const int64_t *mapping,
                              int64_t num_pairs, hipStream_t stream);
 

@@ -34,7 +34,7 @@ def test_header_declares_the_expected_entry_points():
     for must in ("kvc_paged_attention_decode", "kvc_kv_block_copy", "kvc_attn_plan",
                  "kvc_paged_attention_decode_workspace_bytes", "kvc_paged_attention_decode_partial",
                  "kvc_paged_attention_decode_merge", "kvc_validate_attention_inputs",
-                 "kvc_validate_block_mapping", "kvc_status_string", "kvc_version",
+                 "kvc_validate_block_mapping", "kvc_status_string", "kvc_version", "kvc_kv_cache_append",
                  "kvc_last_hip_error"):
         assert must in names
 
@@ -163,6 +163,20 @@ def test_block_copy_argument_errors(K):
     assert call(pool(np=70000, ps=32768 * 100), pool(np=70000, ps=32768 * 100)) == -4
     assert L.kvc_kv_block_copy(None, ctypes.byref(pool()), 0x20000, 1, None) == -1
     assert call(pool(base=None), pool(base=None), m=None, n=0) == 0   # nothing to do
+
+
+def test_cache_append_argument_errors(K):
+    L = K.lib()
+    d = desc(K)
+    g = 0x10000
+    assert L.kvc_kv_cache_append(None, g, g, g, g, g, ctypes.byref(d), None) == -1
+    assert L.kvc_kv_cache_append(g, g, g, g, g, None, ctypes.byref(d), None) == -1
+    assert L.kvc_kv_cache_append(g, g + 4, g, g, g, g, ctypes.byref(d), None) == -6
+    assert L.kvc_kv_cache_append(g, g, g, g, g, g, None, None) == -1
+    bad = desc(K, head_dim=96)
+    assert L.kvc_kv_cache_append(g, g, g, g, g, g, ctypes.byref(bad), None) == -4
+    d0 = desc(K, num_seqs=0)
+    assert L.kvc_kv_cache_append(None, None, None, None, None, None, ctypes.byref(d0), None) == 0
 
 
 def test_binding_refuses_host_tensors(K):

@@ -118,3 +118,57 @@ def test_oracle_swap_round_trip_restores_attention(oracle_mod):
     after = oracle_mod.paged_attention_decode(p["q"], pool1[0], pool1[1], tables, p["lens"],
                                               p["scale"], dtype="f64")
     assert np.array_equal(before, after)
+
+
+# ----------------------------------------------------------------------------
+# cache append
+# ----------------------------------------------------------------------------
+def test_oracle_cache_append_hand_case(oracle_mod):
+    """2 sequences, 1 kv head, D=2, Bs=2, pool of 3 blocks; expectation written by hand."""
+    k_cache = np.zeros((3, 1, 2, 2), dtype=np.float32)
+    v_cache = np.zeros_like(k_cache)
+    tables = np.array([[2, 0], [1, -1]], dtype=np.int32)
+    k_new = np.array([[[1, 2]], [[3, 4]]], dtype=np.float32)
+    v_new = np.array([[[5, 6]], [[7, 8]]], dtype=np.float32)
+    # seq 0 writes position 3 = (table[0][1] = block 0, slot 1); seq 1 writes position 0 = (block 1, slot 0)
+    oracle_mod.kv_cache_append(k_new, v_new, k_cache, v_cache, tables, np.array([3, 0], dtype=np.int32))
+    assert k_cache.tolist() == [[[[0, 0], [1, 2]]], [[[3, 4], [0, 0]]], [[[0, 0], [0, 0]]]]
+    assert v_cache.tolist() == [[[[0, 0], [5, 6]]], [[[7, 8], [0, 0]]], [[[0, 0], [0, 0]]]]
+
+
+def test_oracle_cache_append_matches_numpy_indexing_and_skips_negative(oracle_mod):
+    rng = np.random.default_rng(12)
+    nseq, hkv, d, bs, nb, lmax = 5, 3, 8, 4, 30, 6
+    k_cache = rng.standard_normal((nb, hkv, bs, d)).astype(np.float32)
+    v_cache = rng.standard_normal((nb, hkv, bs, d)).astype(np.float32)
+    tables = rng.permutation(nb)[:nseq * lmax].reshape(nseq, lmax).astype(np.int32)
+    pos = np.array([0, 7, -1, 23, 10], dtype=np.int32)
+    k_new = rng.standard_normal((nseq, hkv, d)).astype(np.float32)
+    v_new = rng.standard_normal((nseq, hkv, d)).astype(np.float32)
+    wk, wv = k_cache.copy(), v_cache.copy()
+    for n in range(nseq):
+        if pos[n] >= 0:
+            wk[tables[n, pos[n] // bs], :, pos[n] % bs, :] = k_new[n]
+            wv[tables[n, pos[n] // bs], :, pos[n] % bs, :] = v_new[n]
+    oracle_mod.kv_cache_append(k_new, v_new, k_cache, v_cache, tables, pos)
+    assert np.array_equal(k_cache, wk) and np.array_equal(v_cache, wv)
+    with pytest.raises(ValueError):
+        oracle_mod.kv_cache_append(k_new, v_new, k_cache, v_cache, tables, np.array([0, 0, 0, 24, 0], dtype=np.int32))
+
+
+def test_oracle_append_then_attend_equals_attention_over_the_longer_sequence(oracle_mod):
+    """Appending token L and attending over L+1 tokens equals attention on a cache built whole."""
+    p = pins.random_problem(13, nseq=3, hq=4, hkv=2, d=8, bs=4, max_ctx=17, nb=40)
+    lens = p["lens"].copy()
+    full = oracle_mod.paged_attention_decode(p["q"], p["k"], p["v"], p["tables"], lens, p["scale"], dtype="f64")
+    k2, v2 = p["k"].copy(), p["v"].copy()
+    last = lens - 1
+    k_new = np.stack([p["k"][p["tables"][n, last[n] // 4], :, last[n] % 4, :] for n in range(3)])
+    v_new = np.stack([p["v"][p["tables"][n, last[n] // 4], :, last[n] % 4, :] for n in range(3)])
+    for n in range(3):                                    # wipe the last token, then append it back
+        k2[p["tables"][n, last[n] // 4], :, last[n] % 4, :] = 99.0
+        v2[p["tables"][n, last[n] // 4], :, last[n] % 4, :] = 99.0
+    oracle_mod.kv_cache_append(np.ascontiguousarray(k_new), np.ascontiguousarray(v_new), k2, v2,
+                               p["tables"], last.astype(np.int32))
+    again = oracle_mod.paged_attention_decode(p["q"], k2, v2, p["tables"], lens, p["scale"], dtype="f64")
+    assert np.array_equal(full, again)
