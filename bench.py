@@ -51,6 +51,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3b", choices=sorted(WORKLOADS))
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA fixed partitions, 3 same with LDS-staged K, 4 MFMA balanced")
     ap.add_argument("--partition-tokens", type=int, default=0)
+    ap.add_argument("--block-size", type=int, default=16, help="tokens per KV block (the configs use 16)")
     ap.add_argument("--replica-bytes", type=float, default=2.2e9,
                     help="rotate over replicas of the batch totalling at least this many KV bytes")
     ap.add_argument("--swap-frac", type=float, default=0.20)
@@ -76,7 +77,7 @@ def main() -> int:
     lib = K.lib()
 
     t0 = time.time()
-    w = W.make_config(args.workload)
+    w = W.make_config(args.workload, block_size=args.block_size)
     log(f"[bench] workload {args.workload}: {w.num_seqs} seqs, mean ctx {w.context_lens.mean():.0f}, "
         f"max {w.max_context_len}, pool {w.num_pool_blocks} blocks, KV {w.kv_bytes()/1e6:.1f} MB "
         f"(generated in {time.time()-t0:.1f}s)")

@@ -241,7 +241,7 @@ def _share_groups(rng: np.random.Generator, context_lens: np.ndarray, block_size
 
 
 def make_config(name: str, *, num_seqs: Optional[int] = None, seed: Optional[int] = None,
-                ctx_scale: float = 1.0) -> PagedWorkload:
+                ctx_scale: float = 1.0, block_size: int = 16) -> PagedWorkload:
     """Build one of the named workloads.
 
     cfg1  tiny fp32 MHA (4 seqs, 8 heads, D 64, ctx U[16,256], pool 128 blocks)
@@ -254,10 +254,14 @@ def make_config(name: str, *, num_seqs: Optional[int] = None, seed: Optional[int
           75 % occupancy (the swap-in needs free slots); extra["swap"] holds the swap-out / swap-in plan for 20 % of sequences
 
     num_seqs / ctx_scale shrink a config for oracle-sized parity cases
-    (ctx_scale multiplies every context length, minimum 1).
+    (ctx_scale multiplies every context length, minimum 1).  block_size other than
+    the configs' 16 serves the block-size sweep (the paper's own default is 8, its
+    analysis runs use 32); the table rows keep their token capacity.
     """
     rng = np.random.default_rng(SEEDS[name] if seed is None else seed)
-    bs = 16
+    bs = block_size
+    assert bs >= 1 and (bs & (bs - 1)) == 0
+    rows = lambda tokens: (tokens + bs - 1) // bs   # table row length for a token capacity
 
     def scaled(c):
         if ctx_scale == 1.0:
@@ -269,32 +273,32 @@ def make_config(name: str, *, num_seqs: Optional[int] = None, seed: Optional[int
         ctx = scaled(rng.integers(16, 257, n).astype(np.int32))
         return build_workload(name, rng, dtype=F32, context_lens=ctx, num_q_heads=8,
                               num_kv_heads=8, head_dim=64, block_size=bs,
-                              max_blocks_per_seq=16, num_pool_blocks=max(128, 16 * n))
+                              max_blocks_per_seq=rows(256), num_pool_blocks=max(128, 16 * n) * 16 // min(bs, 16))
     if name == "cfg2":
         n = num_seqs or 64
         ctx = scaled(lognormal_context_lens(rng, n, 2048))
         return build_workload(name, rng, dtype=BF16, context_lens=ctx, num_q_heads=32,
                               num_kv_heads=32, head_dim=128, block_size=bs,
-                              max_blocks_per_seq=256)
+                              max_blocks_per_seq=rows(4096))
     if name in ("cfg3", "cfg3b"):
         n = num_seqs or (128 if name == "cfg3" else 64)
         ctx = scaled(lognormal_context_lens(rng, n, 4096, 4096))
         return build_workload(name, rng, dtype=BF16, context_lens=ctx, num_q_heads=32,
                               num_kv_heads=8, head_dim=128, block_size=bs,
-                              max_blocks_per_seq=256, occupancy=0.9)
+                              max_blocks_per_seq=rows(4096), occupancy=0.9)
     if name == "cfg4":
         n = num_seqs or 16
         ctx = scaled(rng.integers(8192, 32769, n).astype(np.int32))
         return build_workload(name, rng, dtype=BF16, context_lens=ctx, num_q_heads=64,
                               num_kv_heads=8, head_dim=128, block_size=bs,
-                              max_blocks_per_seq=2048)
+                              max_blocks_per_seq=rows(32768))
     if name == "cfg5":
         n = num_seqs or 96
         ctx = scaled(lognormal_context_lens(rng, n, 4096, 4096))
         groups = _share_groups(rng, ctx, bs, 0.25)
         w = build_workload(name, rng, dtype=BF16, context_lens=ctx, num_q_heads=32,
                            num_kv_heads=8, head_dim=128, block_size=bs,
-                           max_blocks_per_seq=256, occupancy=0.75, share_groups=groups)
+                           max_blocks_per_seq=rows(4096), occupancy=0.75, share_groups=groups)
         w.extra["swap"] = make_swap_plan(rng, w, 0.20)
         return w
     raise KeyError(name)

@@ -45,9 +45,10 @@ bool mfma_ok(const kvc_attn_desc &d) {
 
 // The balanced kernel keeps a prefix sum over the batch in LDS and indexes flat tiles in int32.
 bool balanced_ok(const kvc_attn_desc &d, int max_ctx) {
-    return mfma_ok(d) && d.num_seqs <= kvc::kMaxStreamSeqs &&
+    return d.dtype == KVC_BF16 && d.head_dim == 128 && d.block_size >= 4 &&
+           d.num_q_heads / d.num_kv_heads <= 16 && d.num_seqs <= kvc::kMaxStreamSeqs &&
            int64_t(d.num_seqs) * d.num_kv_heads * ceil_div(max_ctx, 16) < (int64_t(1) << 30) &&
-           int64_t(d.num_pool_blocks) * d.num_kv_heads * (d.block_size / 16) < (int64_t(1) << 31);
+           int64_t(d.num_pool_blocks) * d.num_kv_heads * std::max(1, d.block_size / 16) < (int64_t(1) << 31);
 }
 
 int make_plan(const kvc_attn_desc *d, Plan *pl) {
@@ -74,7 +75,7 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
         kernel = balanced_ok(*d, max_ctx) ? KVC_KERNEL_MFMA_BALANCED
                  : mfma_ok(*d)            ? KVC_KERNEL_MFMA
                                           : KVC_KERNEL_VALU;
-    if (kernel != KVC_KERNEL_VALU && !mfma_ok(*d)) return KVC_ERR_UNSUPPORTED;
+    if ((kernel == KVC_KERNEL_MFMA || kernel == KVC_KERNEL_MFMA_LDS) && !mfma_ok(*d)) return KVC_ERR_UNSUPPORTED;
     if (kernel == KVC_KERNEL_MFMA_BALANCED && !balanced_ok(*d, max_ctx)) return KVC_ERR_UNSUPPORTED;
 
     const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;

@@ -1,5 +1,5 @@
 // Load-balanced persistent partial kernel of paged decode attention on the matrix cores
-// (gfx950, bf16, head_dim 128, block_size a multiple of 16, group <= 16, <= 1024 sequences).
+// (gfx950, bf16, head_dim 128, block_size >= 4, group <= 16, <= 1024 sequences).
 //
 // The serving traces this path sees have heavily skewed context lengths (a lognormal mix:
 // median ~700 tokens, tail to 4096), and the whole batch is only ~30 us of HBM streaming.
@@ -47,7 +47,8 @@ using namespace mfma;
 
 __device__ inline int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-constexpr int kStageTiles = 256;  // tile addresses staged in LDS per wavefront at a time
+constexpr int kStageTiles = 256;  // tiles whose addresses are staged in LDS per wavefront at a time
+constexpr int kMaxUnits = 4;      // a 16-token tile spans up to 4 blocks (block_size 4)
 
 // A row of the flattened work: (sequence, KV head); all fields wavefront-uniform.
 struct RowCursor {
@@ -61,11 +62,11 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
-    AttnParams p, int tiles_per_block_log2) {
+    AttnParams p, int unit_log2, int units_per_block_log2) {
     __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of tiles per sequence (+ guard)
     __shared__ int s_ctx[kMaxStreamSeqs];       // context length per sequence
     __shared__ int s_wave_tot[kWaves];
-    __shared__ int s_tile[kWaves][kStageTiles];  // per worker: (physical 4 KiB tile index) of its next tiles
+    __shared__ int s_tile[kWaves][kStageTiles * kMaxUnits];  // per worker: pool index of each unit of its next tiles
 
     const int tid = threadIdx.x;
     const int wave = uniform(tid >> 6), lane = tid & 63;
@@ -121,7 +122,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const int f0 = worker * C;
     const int NT = min(T, f0 + C) - f0;  // tiles of this worker, >= 1
 
-    const int sub_mask = (1 << tiles_per_block_log2) - 1;
 
     // Row after `c` in flat order, skipping empty sequences.  Past the last row it parks on
     // the guard entry (n == nseq), which is never dereferenced: a cursor only moves there
@@ -158,14 +158,20 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const int first_tile = (f0 - first.pref * Hkv) - first.kvh * first.tiles;
 
     // ---- tile addresses of the worker's range, staged in LDS
-    // Entry k holds the index, in 4 KiB tiles, of the worker's k-th tile inside the KV pools:
-    // (block * Hkv + kv head) * tiles_per_block + tile-in-block.  Staging them up front keeps the
-    // steady-state loop free of dependent block-table loads: the issue side of the pipeline
-    // needs one LDS read per tile and no row bookkeeping at all.
-    const int tiles_per_block = 1 << tiles_per_block_log2;
+    // A "unit" is the part of a 16-token tile that lies in one block: min(block_size, 16)
+    // tokens, so a tile is U = 1, 2 or 4 units.  Entry (k, u) holds the index, in units, of
+    // unit u of the worker's k-th tile inside the KV pools:
+    //   (block * Hkv + kv head) * units_per_block + unit-in-block.
+    // Units past the end of the context (ragged last tile, blocks never allocated) repeat the
+    // last valid unit: they are loaded and masked, never taken from the block table.
+    // Staging the addresses up front keeps the steady-state loop free of dependent
+    // block-table loads: the issue side needs two LDS reads per tile and no row bookkeeping.
+    const int U_log2 = 4 - unit_log2;                 // log2(units per tile)
+    const int unit_tokens = 1 << unit_log2;
+    const int upb_mask = (1 << units_per_block_log2) - 1;
     RowCursor rf = first;           // fill cursor
     int tf = first_tile;            // next tile of row rf to stage
-    int staged_base = 0;            // worker-relative index of s_tile[wave][0]
+    int staged_base = 0;            // worker-relative index of the first staged tile
     auto stage_tiles = [&](int from) __attribute__((always_inline)) {
         const int count = min(kStageTiles, NT - from);
         int off = 0;
@@ -177,10 +183,12 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             if (rf.n >= nseq) break;  // cannot happen for a consistent batch; never walk past the last row
             const int seg = min(rf.tiles - tf, count - off);  // >= 1
             const int32_t *table = block_tables + size_t(rf.n) * p.max_blocks_per_seq;
-            for (int j = lane; j < seg; j += 64) {
-                const int t = tf + j;
-                const int blk = table[t >> tiles_per_block_log2];
-                s_tile[wave][off + j] = (blk * Hkv + rf.kvh) * tiles_per_block + (t & sub_mask);
+            const int last_unit = ((uniform(s_ctx[rf.n]) + unit_tokens - 1) >> unit_log2) - 1;
+            for (int e = lane; e < (seg << U_log2); e += 64) {
+                const int unit = min(((tf << U_log2) + e), last_unit);   // unit index within the row
+                const int blk = table[unit >> units_per_block_log2];
+                s_tile[wave][(off << U_log2) + e] =
+                    ((blk * Hkv + rf.kvh) << units_per_block_log2) + (unit & upb_mask);
             }
             off += seg;
             tf += seg;
@@ -189,11 +197,23 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     };
     stage_tiles(0);
 
+    // Per-lane constants of the tile loads: K wants token r, V wants tokens 4*quad + i.
+    const size_t unit_elems = size_t(unit_tokens) * D;
+    const int k_unit = r >> unit_log2, k_row = r & (unit_tokens - 1);
+    const int v_unit = (4 * quad) >> unit_log2, v_row = (4 * quad) & (unit_tokens - 1);
+    const uint16_t *k_lane = k_cache + k_row * D + 8 * quad;
+    const uint16_t *v_lane = v_cache + v_row * D + 8 * r;
+
     int ki = 0;  // worker-relative index of the next tile to load
     auto issue_next = [&](uint4(&kr)[4], uint4(&vr)[4]) __attribute__((always_inline)) {
         if (ki - staged_base == kStageTiles) stage_tiles(ki);  // very long ranges only
-        const size_t base = size_t(uniform(s_tile[wave][ki - staged_base])) * kTileElems;
-        issue_tile_direct(kr, vr, k_cache + base, v_cache + base, quad, r);
+        const int *e = &s_tile[wave][(ki - staged_base) << U_log2];
+        const uint16_t *kp = k_lane + size_t(e[k_unit]) * unit_elems;
+        const uint16_t *vp = v_lane + size_t(e[v_unit]) * unit_elems;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kr[j] = load16_stream(kp + 32 * j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vr[i] = load16_stream(vp + i * D);
         ++ki;
     };
 
@@ -293,12 +313,17 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
                                       const int32_t *block_tables, const int32_t *context_lens,
                                       void *out, Workspace ws, const AttnParams &p, int grid,
                                       hipStream_t stream) {
-    int tpb_log2 = 0;
-    while ((16 << tpb_log2) < p.block_size) ++tpb_log2;
+    // unit = min(block_size, 16) tokens; blocks hold block_size / unit units
+    int unit_log2 = 4, upb_log2 = 0;
+    if (p.block_size < 16) {
+        unit_log2 = p.block_size_log2;
+    } else {
+        while ((16 << upb_log2) < p.block_size) ++upb_log2;
+    }
     pa_stream_mfma_kernel<<<dim3(grid), dim3(kThreads), 0, stream>>>(
         static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
         static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
-        static_cast<uint16_t *>(out), ws, p, tpb_log2);
+        static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
     return hipGetLastError();
 }
 

@@ -94,6 +94,8 @@ def test_plan_picks_kernels_and_sizes_workspace(K):
                                 max_blocks_per_seq=16))
     assert rc == 0 and p.kernel == K.KERNEL_VALU and p.max_partitions == 1 and p.workspace_bytes == 0
     rc, p = plan_status(K, desc(K, block_size=8))
+    assert rc == 0 and p.kernel == K.KERNEL_MFMA_BALANCED
+    rc, p = plan_status(K, desc(K, block_size=2))
     assert rc == 0 and p.kernel == K.KERNEL_VALU
     rc, p = plan_status(K, desc(K, num_seqs=2000))          # too many sequences for the balanced kernel
     assert rc == 0 and p.kernel == K.KERNEL_MFMA

@@ -129,7 +129,9 @@ def test_block_sizes(oracle_mod, bs):
     if bs >= 16:
         check(w, oracle_mod, f"bs={bs} mfma", kernel=MFMA, partition_tokens=64)
         check(w, oracle_mod, f"bs={bs} mfma lds", kernel=MFMA_LDS, partition_tokens=64)
+    if bs >= 4:
         check(w, oracle_mod, f"bs={bs} balanced", kernel=BALANCED, partition_tokens=16)
+        check(w, oracle_mod, f"bs={bs} balanced auto chunk", kernel=BALANCED)
     wf = custom(105, dtype=W.F32, lens=[5, 70, 131], hq=4, hkv=2, d=64, bs=bs)
     check(wf, oracle_mod, f"bs={bs} f32", partition_tokens=32)
 
@@ -150,6 +152,27 @@ def test_fp32_long_context_stays_within_1e5(oracle_mod):
 def test_maximum_partition_length(oracle_mod, kernel):
     w = custom(108, dtype=W.BF16, lens=[4096, 4095, 8200], hq=4, hkv=1, d=128, bs=16)
     check(w, oracle_mod, "pt=4096", kernel=kernel, partition_tokens=4096)
+
+
+@pytest.mark.parametrize("bs", [4, 8])
+def test_small_blocks_on_the_matrix_core_path(oracle_mod, bs):
+    """block_size 8 (the paper's default) and 4: a 16-token tile spans 2 or 4 blocks, the last
+    tile may touch blocks that were never allocated (table entries poisoned)."""
+    import paper_2503_13773_amd as K
+    lens = [1, 3, 4, 5, 7, 8, 9, 12, 13, 15, 16, 17, 20, 31, 33, 100, 257, 1000]
+    w = custom(150 + bs, dtype=W.BF16, lens=lens, hq=8, hkv=2, d=128, bs=bs)
+    d = to_device(w)
+    assert K.attn_plan(K.attn_desc(d["q"], d["k"], d["tables"])).kernel == BALANCED
+    nblk = W.blocks_needed(w.context_lens, bs)
+    for n in range(w.num_seqs):
+        w.block_tables[n, nblk[n]:] = 2 ** 30 if n % 2 else -1
+        L = int(w.context_lens[n])
+        if L % bs:
+            w.k_cache[w.block_tables[n, nblk[n] - 1], :, L % bs:, :] = np.uint16(0x7FC0)
+            w.v_cache[w.block_tables[n, nblk[n] - 1], :, L % bs:, :] = np.uint16(0x7FC0)
+    for chunk in (0, 16, 48, 160):
+        check(w, oracle_mod, f"bs={bs} chunk={chunk}", kernel=BALANCED, partition_tokens=chunk)
+    check(w, oracle_mod, f"bs={bs} auto")
 
 
 def test_balanced_ranges_longer_than_the_staging_window(oracle_mod):
