@@ -178,7 +178,8 @@ KVC_API int kvc_kv_cache_append(const void *k_new, const void *v_new, void *k_ca
  * blocks of block_bytes bytes; plane p starts at base + p * plane_stride_bytes.
  */
 typedef struct {
-    void *base;                 /* device, 16-byte aligned */
+    void *base;                 /* 16-byte aligned; device memory, or pinned host memory mapped into the
+                                   device address space (hipHostMalloc): swap to / from CPU memory */
     int64_t num_blocks;
     int64_t block_bytes;        /* multiple of 16 */
     int64_t plane_stride_bytes; /* multiple of 16, >= num_blocks * block_bytes (ignored if num_planes == 1) */
@@ -198,6 +199,8 @@ typedef struct {
  *     most once, and when src and dst are the same memory the source and destination block
  *     sets must be disjoint; neither is checked here (see kvc_validate_block_mapping).
  *   - Blocks of dst that are not a destination are left untouched.
+ *   - Either pool may be pinned host memory; the kernel then moves the blocks over PCIe
+ *     itself (no staging copy, one launch for any number of blocks).
  */
 KVC_API int kvc_kv_block_copy(const kvc_pool *src, const kvc_pool *dst, const int64_t *block_mapping,
                       int64_t num_pairs, void *hip_stream);

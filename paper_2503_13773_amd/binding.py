@@ -220,12 +220,36 @@ def kv_cache_append(k_new, v_new, k_cache, v_cache, block_tables, positions, str
                                      ctypes.byref(desc), _stream_handle(stream)), "kvc_kv_cache_append")
 
 
+_hip = None
+
+
+def _device_pointer_of_pinned(t: torch.Tensor) -> int:
+    """Device-side address of a pinned host tensor (asks the HIP runtime; raises if the
+    allocation is not mapped into the device address space)."""
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so.7")   # the runtime torch already loaded (same SONAME)
+        _hip.hipHostGetDevicePointer.restype = ctypes.c_int
+        _hip.hipHostGetDevicePointer.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
+                                                 ctypes.c_uint]
+    dptr = ctypes.c_void_p()
+    rc = _hip.hipHostGetDevicePointer(ctypes.byref(dptr), t.data_ptr(), 0)
+    if rc != 0 or not dptr.value:
+        raise RuntimeError(f"pinned tensor is not device-accessible (hipHostGetDevicePointer -> {rc})")
+    return int(dptr.value)
+
+
 def pool_of(t: torch.Tensor) -> Pool:
-    """View a tensor shaped [num_planes][num_blocks][...] as a kvc_pool."""
-    if not t.is_cuda or not t.is_contiguous() or t.dim() < 3:
-        raise ValueError("pool tensor must be a contiguous device tensor [planes][blocks][...]")
+    """View a tensor shaped [num_planes][num_blocks][...] as a kvc_pool.
+
+    The tensor lives in device memory or in pinned host memory (which the GPU reads and
+    writes over PCIe: the swap-to-CPU-memory path).
+    """
+    if not (t.is_cuda or t.is_pinned()) or not t.is_contiguous() or t.dim() < 3:
+        raise ValueError("pool tensor must be a contiguous device or pinned-host tensor [planes][blocks][...]")
     block_bytes = t[0, 0].numel() * t.element_size()
-    return Pool(base=t.data_ptr(), num_blocks=t.shape[1], block_bytes=block_bytes,
+    base = t.data_ptr() if t.is_cuda else _device_pointer_of_pinned(t)
+    return Pool(base=base, num_blocks=t.shape[1], block_bytes=block_bytes,
                 plane_stride_bytes=t.shape[1] * block_bytes, num_planes=t.shape[0], reserved=0)
 
 

@@ -143,3 +143,30 @@ def test_swap_out_poison_swap_in_round_trip(oracle_mod, full):
                                             w.scale, dtype="bf16", rows=rows, num_threads=4)
     got = run_gpu(w, d2).float().cpu().numpy().astype(np.float64)
     assert max(np.abs(got[s_, h] - ref[s_, h]).max() for s_, h in rows) <= 2e-2
+
+
+def test_swap_to_pinned_host_memory_and_back(oracle_mod):
+    """The swap of the paper moves KV to CPU memory: one pool is pinned host memory that the
+    kernel writes / reads over PCIe.  Both directions bit-exact against the oracle."""
+    import paper_2503_13773_amd as K
+    rng = np.random.default_rng(21)
+    planes, nb, nb_host, bb = 4, 40, 12, 32768
+    dev = rng.integers(0, 256, (planes, nb, bb), dtype=np.uint8)
+    out_map = W.make_copy_mapping(rng, 9, nb, nb_host)
+    host_want = np.zeros((planes, nb_host, bb), dtype=np.uint8)
+    oracle_mod.kv_block_copy(dev, host_want, out_map)
+    tdev = torch.from_numpy(dev).cuda()
+    thost = torch.zeros((planes, nb_host, bb), dtype=torch.uint8, pin_memory=True)
+    K.kv_block_copy(tdev, thost, torch.from_numpy(out_map).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(thost.numpy(), host_want)
+    # back into other device slots
+    free = np.setdiff1d(np.arange(nb), out_map[:, 0])
+    in_map = np.stack([out_map[:, 1], rng.permutation(free)[:9]], axis=1).astype(np.int64)
+    dev_want = dev.copy()
+    oracle_mod.kv_block_copy(host_want, dev_want, in_map)
+    K.kv_block_copy(thost, tdev, torch.from_numpy(in_map).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(tdev.cpu().numpy(), dev_want)
+    with pytest.raises(ValueError):
+        K.pool_of(torch.zeros((planes, nb_host, bb), dtype=torch.uint8))   # pageable host memory is refused

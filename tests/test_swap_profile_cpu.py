@@ -1,0 +1,43 @@
+"""The swap-latency regressor of the preemption-strategy selection (paper Section 3.5):
+least-squares line L_s = gamma * S + delta and the sweet spot where it meets L_r."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2503_13773_amd.swap_profile import fit_linear, r_squared, sweet_spot
+
+
+def test_fit_recovers_an_exact_line():
+    S = [100, 400, 1600, 6400]
+    g, d = fit_linear(S, [0.02 * s + 3.0 for s in S])
+    assert abs(g - 0.02) < 1e-12 and abs(d - 3.0) < 1e-9
+    assert abs(r_squared(S, [0.02 * s + 3.0 for s in S], g, d) - 1.0) < 1e-12
+
+
+def test_fit_matches_numpy_polyfit_on_noisy_data():
+    rng = np.random.default_rng(0)
+    S = np.array([128, 256, 512, 1024, 2048, 4096, 8192], dtype=float)
+    L = 0.0123 * S + 0.4 + rng.normal(0, 0.05, S.size)
+    g, d = fit_linear(S.tolist(), L.tolist())
+    pg, pd = np.polyfit(S, L, 1)
+    assert abs(g - pg) < 1e-10 and abs(d - pd) < 1e-8
+    assert 0.99 < r_squared(S.tolist(), L.tolist(), g, d) <= 1.0
+
+
+def test_fit_rejects_degenerate_input():
+    with pytest.raises(ValueError):
+        fit_linear([5], [1.0])
+    with pytest.raises(ValueError):
+        fit_linear([5, 5, 5], [1.0, 2.0, 3.0])
+
+
+def test_sweet_spot_closed_forms():
+    # quadratic recompute a*S^2 against the line g*S + d: positive root of a S^2 - g S - d = 0
+    a, g, d = 1e-6, 0.002, 1.0
+    want = (g + math.sqrt(g * g + 4 * a * d)) / (2 * a)
+    assert abs(sweet_spot(g, d, a, 2.0) - want) / want < 1e-9
+    # linear recompute k*S against g*S + d with k > g: S = d / (k - g)
+    assert abs(sweet_spot(0.01, 5.0, 0.0, 1.0, kappa_r=0.03) - 250.0) < 1e-6
+    assert sweet_spot(0.01, 0.0, 1.0, 2.0, eps_r=1.0) == 0.0            # swapping always cheaper
+    assert sweet_spot(1.0, 10.0, 1e-12, 1.0) == math.inf                 # recomputation always cheaper
