@@ -51,5 +51,22 @@ def build_library(extra_flags=(), verbose: bool = False) -> str:
     return LIB
 
 
+POLICY_LIB = os.path.join(PKG, "libkvc_policy.so")
+
+
+def build_policy_library(verbose: bool = False) -> str:
+    """The host-side policy core (plain C++, no GPU code)."""
+    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-fvisibility=hidden", "-Wall", "-Werror",
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "policy", "kvc_policy.cpp"),
+           "-o", POLICY_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"g++ failed on kvc_policy.cpp:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print("built", POLICY_LIB)
+    return POLICY_LIB
+
+
 if __name__ == "__main__":
     build_library(sys.argv[1:], verbose=True)
+    build_policy_library(verbose=True)
