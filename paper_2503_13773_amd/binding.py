@@ -11,7 +11,8 @@ KVC_F32, KVC_BF16 = 0, 1
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS, KERNEL_MFMA_BALANCED = 0, 1, 2, 3, 4
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libkvc_hip.so")
+# KVC_HIP_LIBRARY points at another build of the same library (A/B comparisons of kernels)
+_LIB_PATH = os.environ.get("KVC_HIP_LIBRARY") or os.path.join(_PKG, "libkvc_hip.so")
 _lib = None
 
 
