@@ -53,6 +53,11 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
             ctypes.c_int64]
+        lib.oracle_paged_attention_prefill.restype = ctypes.c_int
+        lib.oracle_paged_attention_prefill.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_num_threads_available.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -159,3 +164,36 @@ def kv_cache_append(k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v
                                     block_tables.shape[1], nb)
     if rc != 0:
         raise ValueError("position or block id out of range")
+
+
+def paged_attention_prefill(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+                            block_tables: np.ndarray, context_lens: np.ndarray, q_start: np.ndarray,
+                            scale: float, *, dtype: str, num_threads: int = 1) -> np.ndarray:
+    """Causal attention of the last Qn = q_start[n+1]-q_start[n] positions of every sequence over
+    its block list, in fp64.  q [total_q][Hq][D]; returns float64 [total_q][Hq][D]."""
+    lib = _load()
+    npdt = _NP[dtype]
+    q = np.ascontiguousarray(q, dtype=npdt)
+    k_cache = np.ascontiguousarray(k_cache, dtype=npdt)
+    v_cache = np.ascontiguousarray(v_cache, dtype=npdt)
+    block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+    context_lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    q_start = np.ascontiguousarray(q_start, dtype=np.int32)
+    total_q, hq, d = q.shape
+    nb, hkv, bs, d2 = k_cache.shape
+    nseq = context_lens.shape[0]
+    assert d2 == d and v_cache.shape == k_cache.shape and q_start.shape == (nseq + 1,)
+    assert q_start[0] == 0 and q_start[-1] == total_q
+    nblk = (context_lens.astype(np.int64) + bs - 1) // bs
+    for n in range(nseq):
+        used = block_tables[n, :nblk[n]]
+        if used.size and (used.min() < 0 or used.max() >= nb):
+            raise ValueError(f"sequence {n}: block id outside the pool")
+    out = np.zeros((total_q, hq, d), dtype=np.float64)
+    rc = lib.oracle_paged_attention_prefill(
+        q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data, block_tables.ctypes.data,
+        context_lens.ctypes.data, q_start.ctypes.data, float(scale), out.ctypes.data, _DT[dtype],
+        nseq, hq, hkv, d, bs, block_tables.shape[1], int(num_threads))
+    if rc != 0:
+        raise ValueError("oracle_paged_attention_prefill rejected its arguments")
+    return out

@@ -230,3 +230,91 @@ int oracle_kv_cache_append(const uint8_t *k_new, const uint8_t *v_new, uint8_t *
     }
     return 0;
 }
+
+/*
+ * Causal attention of several query positions per sequence over the block-allocated cache:
+ * the recomputation path of a preempted request re-runs prefill over its prompt and generated
+ * tokens (Section 2.5 and 3.5: cost quadratic in the sequence length), and chunked prefill
+ * attends a chunk of new positions to everything before it.
+ *
+ * Sequence n has S = context_lens[n] tokens in the cache and Qn = q_start[n+1] - q_start[n]
+ * query rows; query row i sits at position pos = S - Qn + i and attends to tokens 0 .. pos:
+ *   s[t] = scale * q . K[t],  p = softmax over t <= pos,  out = sum_t p[t] V[t]      (fp64)
+ * With Qn == 1 this is the decode definition above.  Returns -1 on inconsistent arguments
+ * (Qn > S, negative sizes).
+ * q, out: [total_q][num_q_heads][head_dim] (out in doubles).
+ */
+int oracle_paged_attention_prefill(const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   const int32_t *q_start, double scale, double *out, int dtype,
+                                   int num_seqs, int num_q_heads, int num_kv_heads, int head_dim,
+                                   int block_size, int max_blocks_per_seq, int num_threads)
+{
+    if (num_kv_heads <= 0 || num_q_heads % num_kv_heads != 0 || head_dim <= 0 || block_size <= 0)
+        return -1;
+    int max_len = 1;
+    for (int n = 0; n < num_seqs; ++n) {
+        int S = context_lens[n], Qn = q_start[n + 1] - q_start[n];
+        if (S < 0 || Qn < 0 || Qn > S || S > (int64_t)max_blocks_per_seq * block_size)
+            return -1;
+        if (S > max_len)
+            max_len = S;
+    }
+    const int group = num_q_heads / num_kv_heads;
+    int failed = 0;
+    if (num_threads < 1)
+        num_threads = 1;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(num_threads)
+#endif
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)max_len);
+        if (!s) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+        for (int n = 0; n < num_seqs && s; ++n) {
+            const int S = context_lens[n], Qn = q_start[n + 1] - q_start[n];
+            const int32_t *table = block_tables + (int64_t)n * max_blocks_per_seq;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1) nowait
+#endif
+            for (int64_t r = 0; r < (int64_t)Qn * num_q_heads; ++r) {
+                const int i = (int)(r / num_q_heads), h = (int)(r % num_q_heads), g = h / group;
+                const int pos = S - Qn + i;
+                const int64_t qbase = (((int64_t)q_start[n] + i) * num_q_heads + h) * head_dim;
+                double *o = out + qbase;
+                for (int t = 0; t <= pos; ++t) {
+                    int64_t blk = table[t / block_size];
+                    double dot = 0.0;
+                    for (int d = 0; d < head_dim; ++d)
+                        dot += widen(q, qbase + d, dtype) *
+                               widen(k_cache, pool_index(blk, g, t % block_size, d, num_kv_heads, block_size, head_dim), dtype);
+                    s[t] = scale * dot;
+                }
+                double m = s[0];
+                for (int t = 1; t <= pos; ++t)
+                    if (s[t] > m)
+                        m = s[t];
+                double Z = 0.0;
+                for (int t = 0; t <= pos; ++t) {
+                    s[t] = exp(s[t] - m);
+                    Z += s[t];
+                }
+                for (int d = 0; d < head_dim; ++d)
+                    o[d] = 0.0;
+                for (int t = 0; t <= pos; ++t) {
+                    int64_t blk = table[t / block_size];
+                    for (int d = 0; d < head_dim; ++d)
+                        o[d] += s[t] * widen(v_cache, pool_index(blk, g, t % block_size, d, num_kv_heads, block_size, head_dim), dtype);
+                }
+                for (int d = 0; d < head_dim; ++d)
+                    o[d] /= Z;
+            }
+        }
+        free(s);
+    }
+    return failed ? -1 : 0;
+}

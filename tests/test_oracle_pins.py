@@ -172,3 +172,75 @@ def test_oracle_append_then_attend_equals_attention_over_the_longer_sequence(ora
                                p["tables"], last.astype(np.int32))
     again = oracle_mod.paged_attention_decode(p["q"], k2, v2, p["tables"], lens, p["scale"], dtype="f64")
     assert np.array_equal(full, again)
+
+
+# ----------------------------------------------------------------------------
+# causal (prefill / recompute) attention
+# ----------------------------------------------------------------------------
+def prefill_problem(seed, lens, qlens, hq=4, hkv=2, d=8, bs=4):
+    p = pins.random_problem(seed, lens=lens, hq=hq, hkv=hkv, d=d, bs=bs)
+    q_start = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
+    p["q"] = np.random.default_rng(seed + 1).standard_normal((int(q_start[-1]), hq, d))
+    p["q_start"] = q_start
+    return p
+
+
+def test_oracle_prefill_matches_dense_causal_bruteforce(oracle_mod):
+    """Masked softmax with matrix ops + scipy on the un-paged sequence."""
+    import scipy.special
+    p = prefill_problem(201, lens=[13, 7, 20], qlens=[13, 3, 1])
+    out = oracle_mod.paged_attention_prefill(p["q"], p["k"], p["v"], p["tables"], p["lens"], p["q_start"],
+                                             p["scale"], dtype="f64")
+    for n in range(3):
+        Kd, Vd = pins.gather_dense(p, n)                                   # [S][Hkv][D]
+        S, Qn = int(p["lens"][n]), int(p["q_start"][n + 1] - p["q_start"][n])
+        qn = p["q"][p["q_start"][n]:p["q_start"][n + 1]]                   # [Qn][Hq][D]
+        Kh, Vh = np.repeat(Kd, 2, axis=1), np.repeat(Vd, 2, axis=1)        # [S][Hq][D]
+        sc = np.einsum("qhd,shd->hqs", qn, Kh) * p["scale"]
+        pos = S - Qn + np.arange(Qn)
+        sc = np.where(np.arange(S)[None, None, :] <= pos[None, :, None], sc, -np.inf)
+        ref = np.einsum("hqs,shd->qhd", scipy.special.softmax(sc, axis=2), Vh)
+        assert np.abs(out[p["q_start"][n]:p["q_start"][n + 1]] - ref).max() < 1e-12
+
+
+def test_oracle_prefill_matches_library_causal_attention(oracle_mod):
+    """torch scaled_dot_product_attention(is_causal=True), fp64, full recompute (Qn == S)."""
+    import torch
+    import torch.nn.functional as F
+    p = prefill_problem(202, lens=[11], qlens=[11], hq=2, hkv=2, d=16)
+    out = oracle_mod.paged_attention_prefill(p["q"], p["k"], p["v"], p["tables"], p["lens"], p["q_start"],
+                                             p["scale"], dtype="f64")
+    Kd, Vd = pins.gather_dense(p, 0)
+    qh = torch.from_numpy(p["q"]).permute(1, 0, 2)[None]                   # [1][H][S][D]
+    kh = torch.from_numpy(Kd).permute(1, 0, 2)[None]
+    vh = torch.from_numpy(Vd).permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(qh, kh, vh, is_causal=True, scale=p["scale"])[0].permute(1, 0, 2).numpy()
+    assert np.abs(out - ref).max() < 1e-12
+
+
+def test_oracle_prefill_special_cases(oracle_mod):
+    p = prefill_problem(203, lens=[9, 14], qlens=[9, 5])
+    out = oracle_mod.paged_attention_prefill(p["q"], p["k"], p["v"], p["tables"], p["lens"], p["q_start"],
+                                             p["scale"], dtype="f64")
+    # position 0 sees one token: its v, bit-exactly
+    for h in range(4):
+        assert np.array_equal(out[0, h], p["v"][p["tables"][0, 0], h // 2, 0])
+    # the last query row of every sequence equals decode attention with that row as the query
+    last = p["q"][[8, 13]]
+    dec = oracle_mod.paged_attention_decode(last, p["k"], p["v"], p["tables"], p["lens"], p["scale"], dtype="f64")
+    assert np.abs(out[[8, 13]] - dec).max() < 1e-15
+    # an earlier row equals decode attention over the truncated context
+    dec5 = oracle_mod.paged_attention_decode(p["q"][[5]], p["k"], p["v"], p["tables"][:1],
+                                             np.array([6], dtype=np.int32), p["scale"], dtype="f64")
+    assert np.abs(out[5] - dec5[0]).max() < 1e-15
+    # causality: changing tokens after position 4 of sequence 0 leaves rows 0..4 unchanged
+    k2, v2 = p["k"].copy(), p["v"].copy()
+    for t in range(5, 9):
+        k2[p["tables"][0, t // 4], :, t % 4] += 3.0
+        v2[p["tables"][0, t // 4], :, t % 4] -= 5.0
+    out2 = oracle_mod.paged_attention_prefill(p["q"], k2, v2, p["tables"], p["lens"], p["q_start"],
+                                              p["scale"], dtype="f64")
+    assert np.array_equal(out[:5], out2[:5]) and np.abs(out[5:9] - out2[5:9]).max() > 1e-3
+    with pytest.raises(ValueError):
+        oracle_mod.paged_attention_prefill(p["q"], p["k"], p["v"], p["tables"], np.array([4, 14], dtype=np.int32),
+                                           p["q_start"], p["scale"], dtype="f64")   # more queries than context
