@@ -158,6 +158,28 @@ KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int
                                   const kvc_attn_desc *desc, void *hip_stream);
 
 /*
+ * Causal attention of several query positions per sequence over the block-allocated cache: the
+ * recomputation path of a preempted request (prefill re-run over its prompt and generated tokens;
+ * Section 2.5 and 3.5: cost quadratic in the sequence length) and chunked prefill.
+ *   q, out        T [total_q][num_q_heads][head_dim], the query rows of all sequences back to back
+ *   q_start       int32 [num_seqs + 1] (device): sequence n owns rows q_start[n] .. q_start[n+1]-1
+ *   context_lens  int32 [num_seqs] (device): tokens of sequence n present in the cache (S_n);
+ *                 its Qn query rows sit at positions S_n - Qn .. S_n - 1 and row i attends to
+ *                 tokens 0 .. (S_n - Qn + i).  Qn <= S_n; a sequence with Qn == 0 is skipped.
+ *   total_q, max_query_len   host-known: number of rows of q, and an upper bound on Qn (sizes
+ *                 the launch grid; rows of sequences with Qn > max_query_len beyond it are not
+ *                 computed).
+ * Supported: bf16, head_dim 128, block_size a multiple of 16, group <= 16, contexts <= 32768
+ * tokens; everything else returns KVC_ERR_UNSUPPORTED.  No workspace.  desc->max_context_len,
+ * partition_tokens and kernel are ignored (must be valid).
+ */
+KVC_API int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *v_cache,
+                                        const int32_t *block_tables, const int32_t *context_lens,
+                                        const int32_t *q_start, float scale, void *out,
+                                        const kvc_attn_desc *desc, int32_t total_q,
+                                        int32_t max_query_len, void *hip_stream);
+
+/*
  * Write one new token per sequence into the block-allocated cache (the step that precedes
  * the decode attention of an iteration: every running request produces one token whose K and V
  * land in the next free slot of its last block; Section 1, Section 3.3).

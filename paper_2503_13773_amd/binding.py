@@ -75,6 +75,9 @@ def lib():
     L.kvc_paged_attention_decode_merge.argtypes = [i32p, vp, dp, vp, sz, vp]
     L.kvc_validate_attention_inputs.restype = ctypes.c_int
     L.kvc_validate_attention_inputs.argtypes = [i32p, i32p, dp, vp]
+    L.kvc_paged_attention_prefill.restype = ctypes.c_int
+    L.kvc_paged_attention_prefill.argtypes = [vp, vp, vp, i32p, i32p, i32p, f, vp, dp, ctypes.c_int32,
+                                              ctypes.c_int32, vp]
     L.kvc_kv_cache_append.restype = ctypes.c_int
     L.kvc_kv_cache_append.argtypes = [vp, vp, vp, vp, i32p, i32p, dp, vp]
     L.kvc_kv_block_copy.restype = ctypes.c_int
@@ -198,6 +201,36 @@ def validate_attention_inputs(block_tables, context_lens, desc: AttnDesc, stream
     """Blocking range check of the index arrays; returns the status (0 = fine)."""
     return int(lib().kvc_validate_attention_inputs(block_tables.data_ptr(), context_lens.data_ptr(),
                                                    ctypes.byref(desc), _stream_handle(stream)))
+
+
+def paged_attention_prefill(q, k_cache, v_cache, block_tables, context_lens, q_start, scale: float,
+                            max_query_len: int, out=None, stream=None):
+    """Causal attention of the last Qn = q_start[n+1]-q_start[n] positions of every sequence
+    (q is [total_q][Hq][D], rows of all sequences back to back) over its block list."""
+    for t in (q, k_cache, v_cache, block_tables, context_lens, q_start):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    if q_start.dtype != torch.int32 or q_start.shape != (context_lens.shape[0] + 1,):
+        raise TypeError("q_start must be int32 [num_seqs + 1]")
+    if block_tables.dtype != torch.int32 or context_lens.dtype != torch.int32:
+        raise TypeError("block_tables and context_lens must be int32")
+    if v_cache.shape != k_cache.shape or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise ValueError("k_cache / v_cache must match each other and q's dtype")
+    total_q, hq, d = q.shape
+    nb, hkv, bs, d2 = k_cache.shape
+    if d2 != d or block_tables.shape[0] != context_lens.shape[0]:
+        raise ValueError("shapes do not match")
+    if out is None:
+        out = torch.empty_like(q)
+    desc = AttnDesc(num_seqs=context_lens.shape[0], num_q_heads=hq, num_kv_heads=hkv, head_dim=d,
+                    block_size=bs, max_blocks_per_seq=block_tables.shape[1], num_pool_blocks=nb,
+                    dtype=_dtype_code(q), max_context_len=0, partition_tokens=0, kernel=KERNEL_AUTO,
+                    reserved=0)
+    _check(lib().kvc_paged_attention_prefill(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
+        context_lens.data_ptr(), q_start.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc),
+        int(total_q), int(max_query_len), _stream_handle(stream)), "kvc_paged_attention_prefill")
+    return out
 
 
 def kv_cache_append(k_new, v_new, k_cache, v_cache, block_tables, positions, stream=None) -> None:

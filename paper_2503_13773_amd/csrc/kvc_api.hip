@@ -353,6 +353,39 @@ int kvc_validate_attention_inputs(const int32_t *block_tables, const int32_t *co
     return KVC_OK;
 }
 
+int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *block_tables, const int32_t *context_lens,
+                                const int32_t *q_start, float scale, void *out,
+                                const kvc_attn_desc *desc, int32_t total_q, int32_t max_query_len,
+                                void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (total_q < 0 || max_query_len < 0) return KVC_ERR_BAD_SHAPE;
+    if (!mfma_ok(*desc) || int64_t(desc->max_blocks_per_seq) * desc->block_size > 32768)
+        return KVC_ERR_UNSUPPORTED;
+    if (desc->num_seqs == 0 || total_q == 0 || max_query_len == 0) return KVC_OK;
+    if (!q_start) return KVC_ERR_NULL;
+    rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
+    if (rc != KVC_OK) return rc;
+    kvc::PrefillParams p;
+    p.num_seqs = desc->num_seqs;
+    p.num_q_heads = desc->num_q_heads;
+    p.num_kv_heads = desc->num_kv_heads;
+    p.group = desc->num_q_heads / desc->num_kv_heads;
+    p.heads_per_chunk = p.group % 4 == 0 ? 4 : p.group % 2 == 0 ? 2 : 1;
+    p.block_size = desc->block_size;
+    p.tiles_per_block_log2 = ilog2(desc->block_size / 16);
+    p.max_blocks_per_seq = desc->max_blocks_per_seq;
+    p.max_query_tiles = int(ceil_div(max_query_len, 64));
+    p.scale_log2e = float(double(scale) * 1.4426950408889634);
+    if (int64_t(p.num_q_heads / p.heads_per_chunk) * p.num_seqs * p.max_query_tiles > kMaxGrid)
+        return KVC_ERR_BAD_SHAPE;
+    const hipError_t e = kvc::launch_prefill_mfma(q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                  out, p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
 int kvc_kv_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                         const int32_t *block_tables, const int32_t *positions,
                         const kvc_attn_desc *desc, void *hip_stream) {

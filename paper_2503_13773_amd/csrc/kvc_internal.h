@@ -25,6 +25,20 @@ struct AttnParams {
     float scale_log2e;      // scale * log2(e), for the base-2 softmax of the MFMA kernel
 };
 
+// Causal multi-query (prefill / recompute) attention.
+struct PrefillParams {
+    int num_seqs;
+    int num_q_heads;
+    int num_kv_heads;
+    int group;                 // num_q_heads / num_kv_heads
+    int heads_per_chunk;       // query heads one wavefront carries (1, 2 or 4; divides group)
+    int block_size;
+    int tiles_per_block_log2;  // log2(block_size / 16)
+    int max_blocks_per_seq;
+    int max_query_tiles;       // ceil(max_query_len / 64)
+    float scale_log2e;
+};
+
 // Workspace layout: acc [num_seqs][num_q_heads][max_partitions][head_dim] fp32, then
 // ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum), then
 // (balanced kernel only) cnt [num_seqs][num_kv_heads] int32 = partials per row; each array
@@ -58,6 +72,10 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
                         int dtype, int head_dim, bool base2, bool counted, int grid,
                         hipStream_t stream);
+hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               const int32_t *q_start, void *out, const PrefillParams &p,
+                               hipStream_t stream);
 hipError_t launch_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                                const int32_t *block_tables, const int32_t *positions, int num_seqs,
                                int num_kv_heads, int row_bytes, int block_size_log2,

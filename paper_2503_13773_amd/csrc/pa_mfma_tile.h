@@ -158,5 +158,69 @@ __device__ inline void compute_tile(HeadState &st, const bf16x8 (&ka)[4], uint4 
     }
 }
 
+// Several 16-column groups against the same K/V tile (prefill: the groups are the query heads
+// that share the KV head, their 16 columns are 16 query positions).  The K operand and the
+// register transpose of V are shared by the groups; each group keeps its own softmax state.
+// `valid` = tokens of the tile inside the context (wavefront-uniform, zeroes V rows past it);
+// `limit` = tokens of the tile visible to this lane's column (causal mask; may be <= 0, the
+// column must already hold a finite running max then).
+template <int NG>
+__device__ inline void compute_tile_groups(HeadState (&st)[NG], const bf16x8 (&ka)[4], uint4 (&vr)[4],
+                                           const bf16x8 (&qb)[NG][4], float scale_log2e, int valid,
+                                           int limit, int quad) {
+    if (valid < kTileTokens) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * quad + i >= valid) vr[i] = uint4{0u, 0u, 0u, 0u};
+    }
+    shortx4 pb[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        floatx4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j], qb[g][j], s, 0, 0, 0);
+        float sv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[i] = (4 * quad + i < limit) ? s[i] * scale_log2e : -INFINITY;
+        float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(st[g].m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
+        st[g].m = m_new;
+        float pf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pf[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
+        const uint32_t p01 = pack_bf16(pf[0], pf[1]);
+        const uint32_t p23 = pack_bf16(pf[2], pf[3]);
+        const float psum = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
+                           (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
+        st[g].l = fmaf(st[g].l, alpha, psum);
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[g].acc[e] *= alpha;
+        }
+        const uint2 pw = {p01, p23};
+        pb[g] = __builtin_bit_cast(shortx4, pw);
+    }
+    const uint32_t v0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
+    const uint32_t v1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
+    const uint32_t v2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
+    const uint32_t v3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint2 lo = {__builtin_amdgcn_perm(v1[w], v0[w], 0x05040100u),
+                          __builtin_amdgcn_perm(v3[w], v2[w], 0x05040100u)};
+        const uint2 hi = {__builtin_amdgcn_perm(v1[w], v0[w], 0x07060302u),
+                          __builtin_amdgcn_perm(v3[w], v2[w], 0x07060302u)};
+        const shortx4 alo = __builtin_bit_cast(shortx4, lo), ahi = __builtin_bit_cast(shortx4, hi);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            st[g].acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(alo, pb[g], st[g].acc[2 * w], 0, 0, 0);
+            st[g].acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ahi, pb[g], st[g].acc[2 * w + 1], 0, 0, 0);
+        }
+    }
+}
+
 }  // namespace mfma
 }  // namespace kvc
