@@ -1,0 +1,95 @@
+"""Profile the attention part of recomputation against sequence length on MI355X.
+
+The paper's preemption-strategy selection (Section 3.5) fits a polynomial regressor
+L_r(S) = alpha * S^beta + kappa * S + eps to profiled recomputation times and compares it with
+the linear swap regressor.  Recomputation re-runs prefill over the preempted request's S tokens;
+this module times the part of it that is on this library's path - causal attention over the
+paged KV cache, `paged_attention_prefill`, for every layer - reports the achieved MFMA rate and
+fits the power law alpha * S^beta by least squares in log-log space.  The dense projections
+and MLPs of a full prefill are outside this library, so the figure is a lower bound on L_r.
+
+    python -m paper_2503_13773_amd.recompute_profile [--layers 32] [--q-heads 32] [--kv-heads 8]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+from typing import Dict, List, Sequence, Tuple
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def fit_power_law(S: Sequence[float], L: Sequence[float]) -> Tuple[float, float]:
+    """Least squares of log L = log alpha + beta log S: returns (alpha, beta)."""
+    if len(S) < 2 or len(S) != len(L) or min(S) <= 0 or min(L) <= 0:
+        raise ValueError("need at least two positive (S, L) samples")
+    xs = [math.log(s) for s in S]
+    ys = [math.log(l) for l in L]
+    n = len(xs)
+    mx, my = sum(xs) / n, sum(ys) / n
+    sxx = sum((x - mx) ** 2 for x in xs)
+    if sxx == 0:
+        raise ValueError("all sequence lengths are equal")
+    beta = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sxx
+    return math.exp(my - beta * mx), beta
+
+
+def causal_attention_flops(S: int, q_heads: int, head_dim: int) -> float:
+    """QK^T and PV multiply-adds over the causal triangle: 4 * D * Hq * S (S + 1) / 2."""
+    return 4.0 * head_dim * q_heads * S * (S + 1) / 2.0
+
+
+def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int = 32, kv_heads: int = 8,
+                      head_dim: int = 128, block_size: int = 16, reps: int = 5, seed: int = 0) -> Dict:
+    import torch
+
+    from . import binding as K
+
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    smax = max(seq_lens)
+    nb = (smax + block_size - 1) // block_size + 8
+    k_cache = torch.randn((nb, kv_heads, block_size, head_dim), generator=gen).to(torch.bfloat16).cuda()
+    v_cache = torch.randn((nb, kv_heads, block_size, head_dim), generator=gen).to(torch.bfloat16).cuda()
+    q_all = torch.randn((smax, q_heads, head_dim), generator=gen).to(torch.bfloat16).cuda()
+    table = torch.randperm(nb, generator=gen)[None, :].to(torch.int32).cuda()
+    stream = torch.cuda.current_stream()
+    samples: List[Dict] = []
+    for S in seq_lens:
+        q = q_all[:S].contiguous()
+        lens = torch.tensor([S], dtype=torch.int32, device="cuda")
+        qs = torch.tensor([0, S], dtype=torch.int32, device="cuda")
+        out = torch.empty_like(q)
+        scale = 1.0 / math.sqrt(head_dim)
+        K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(reps):
+            K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        fl = causal_attention_flops(S, q_heads, head_dim)
+        samples.append({"S": int(S), "layer_ms": ms, "all_layers_ms": ms * layers,
+                        "tflops": fl / ms / 1e9, "frac_of_mfma_peak": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS})
+    alpha, beta = fit_power_law([s["S"] for s in samples], [s["all_layers_ms"] for s in samples])
+    return {"model": {"layers": layers, "q_heads": q_heads, "kv_heads": kv_heads, "head_dim": head_dim,
+                      "block_size": block_size}, "samples": samples, "alpha_ms": alpha, "beta": beta}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--q-heads", type=int, default=32)
+    ap.add_argument("--kv-heads", type=int, default=8)
+    ap.add_argument("--seq-lens", type=int, nargs="+", default=[256, 512, 1024, 2048, 4096, 8192, 16384])
+    ap.add_argument("--reps", type=int, default=5)
+    args = ap.parse_args()
+    print(json.dumps(profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads,
+                                       kv_heads=args.kv_heads, reps=args.reps)))
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())

@@ -41,3 +41,17 @@ def test_sweet_spot_closed_forms():
     assert abs(sweet_spot(0.01, 5.0, 0.0, 1.0, kappa_r=0.03) - 250.0) < 1e-6
     assert sweet_spot(0.01, 0.0, 1.0, 2.0, eps_r=1.0) == 0.0            # swapping always cheaper
     assert sweet_spot(1.0, 10.0, 1e-12, 1.0) == math.inf                 # recomputation always cheaper
+
+
+def test_power_law_fit_and_flop_count():
+    from paper_2503_13773_amd.recompute_profile import causal_attention_flops, fit_power_law
+    S = [256, 512, 1024, 2048, 4096]
+    a, b = fit_power_law(S, [3e-6 * s ** 1.8 for s in S])
+    assert abs(b - 1.8) < 1e-12 and abs(a - 3e-6) / 3e-6 < 1e-9
+    pa, pb = np.polyfit(np.log(S), np.log([2.0 * s ** 2 + 5 * s for s in S]), 1)[::-1]
+    a, b = fit_power_law(S, [2.0 * s ** 2 + 5 * s for s in S])
+    assert abs(b - pb) < 1e-10 and abs(math.log(a) - pa) < 1e-9
+    # one head, D = 1, S = 3: rows see 1, 2, 3 tokens -> 6 (q.k) + 6 (p.v) multiply-adds = 24 flops
+    assert causal_attention_flops(3, 1, 1) == 24.0
+    with pytest.raises(ValueError):
+        fit_power_law([4, 4], [1.0, 2.0])
