@@ -33,7 +33,7 @@ using namespace mfma;
 constexpr int kMaxPrefillTiles = 2048;  // 32768 tokens
 
 template <int NG>
-__global__ __launch_bounds__(kThreads, 1) void pa_prefill_mfma_kernel(
+__global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
