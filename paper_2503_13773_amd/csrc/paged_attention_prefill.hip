@@ -4,21 +4,36 @@
 // sequence length: paper Section 2.5 and 3.5) and chunked prefill.
 //
 // Bound: MFMA (4 * D * Hq * sum over query rows of (position + 1) flops), not HBM: every K/V
-// tile is used by 16 query positions x the query heads that share the KV head.
+// tile is used by 64 query positions x the query heads that share the KV head.
 //
 // One workgroup = (sequence, chunk of NG query heads sharing one KV head, 64 consecutive query
-// rows); each of its 4 wavefronts owns 16 query rows and walks the K/V tiles from token 0 to
-// its last visible token with the same two-register-set software pipeline as the decode
-// kernels.  Per tile a wavefront computes, for every one of its NG heads, S = K . Q^T with the
-// 16 query rows as the 16 columns of the MFMA tile, an online softmax per column, and
-// O^T += V^T . P^T (per-tile code in pa_mfma_tile.h); the K operand and the register
-// transpose of V are shared by the NG heads.  The causal mask only bites in the one or two
-// tiles on the diagonal; it is a per-lane row limit.  Token 0 is visible to every query row and
-// tiles are walked in order, so every column has a finite running max after the first tile.
-// Workgroups with the most tiles (the last query rows) are dispatched first.
+// rows); each of its 4 wavefronts owns 16 query rows (the 16 columns of its MFMA tiles) for the
+// NG heads.  The workgroup walks the context in steps of 32 tokens.  The K and V rows of a
+// step are fetched from the cache once per workgroup (4 x 16 bytes per lane, 1 KiB contiguous
+// per load instruction), parked in LDS, and read from there by all four wavefronts as MFMA
+// operands: measured with one private copy per wavefront, the vector memory pipeline (about 40
+// cache look-ups per 16-byte-per-lane load instruction) was busy 92 % of the time and bound the
+// kernel.  LDS holds two steps, so the loads of step s+2 are in flight and step s+1 is being
+// written while step s is consumed; one barrier per step.
 //
-// The block ids of the sequence are staged in LDS once per workgroup (contexts up to 32768
-// tokens).
+// Per step and head: S = K . Q^T for the two 16-token tiles (8 x v_mfma_f32_16x16x32_bf16),
+// one online-softmax update over the 32 tokens, and O^T += V^T . P^T with the 32 tokens as the
+// depth of 8 more 32-deep MFMAs: the C layout of the two score tiles (lane holds tokens
+// 4*quad + i of each) is taken as the B operand as it stands, which fixes the order in which
+// the 32 tokens fill the depth slots (slot 8*quad + i = token 4*quad + i of the first tile,
+// slot 8*quad + 4 + i the same of the second); the register transpose of V (shared by the NG
+// heads) builds its A operand in the same order.  The running sum of the weights is one more
+// MFMA against an all-ones A operand, so it adds up exactly the bf16-rounded weights that
+// multiply V and needs no cross-lane reduction.  K rows are stored in LDS with their 16-byte
+// chunks XOR-permuted by the row number, which makes the A-operand reads (16 lanes = 16 rows,
+// same columns) conflict free; V is read row-wise and needs no permutation.
+//
+// The causal mask only bites in the last one or two steps of a wavefront: steps entirely
+// below the diagonal of all 16 rows run code without mask or range checks.  Token 0 is visible
+// to every query row and steps are walked in order, so every column has a finite running max
+// after the first step.  Workgroups with the most steps (the last query rows) are dispatched
+// first.  The block ids of the sequence are staged in LDS once per workgroup (contexts up to
+// 32768 tokens).
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -31,6 +46,123 @@ namespace {
 using namespace mfma;
 
 constexpr int kMaxPrefillTiles = 2048;  // 32768 tokens
+constexpr int kStepTiles = 2;
+constexpr int kStepTokens = kStepTiles * kTileTokens;
+constexpr int kStepElems = kStepTiles * kTileElems;
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// Online-softmax state of one head: 16 query rows (columns r) x 128 dims as in the decode tile
+// code (lane (quad, r) holds O[row r][32*quad .. +31], element 8i + e in acc[e][i]).
+struct PrefillState {
+    floatx4 acc[8];
+    floatx4 lsum;  // every entry: running sum of the rounded weights of column r
+    float m;       // running max of the scaled scores (base-2 units) of column r
+
+    __device__ inline void reset() {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+        lsum = floatx4{0.f, 0.f, 0.f, 0.f};
+        m = -INFINITY;
+    }
+};
+
+// max over the four lanes that share r (lane = 16*quad + r): the two row swaps exchange 16-lane
+// rows between the two copies of the operand, no LDS round trip.
+__device__ inline float max_over_quads(float x) {
+    const unsigned u = __float_as_uint(x);
+    const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const unsigned w = __float_as_uint(y);
+    const u32x2 b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+// One 32-token step of NG heads from the K/V rows parked in LDS (sk, sv: [32 tokens][128]).
+// MASKED: `valid` = tokens of the step inside the context (wavefront-uniform; V rows past it are
+// zeroed so that NaN stored there cannot reach the output), `limit` = tokens of the step visible
+// to this lane's column (may be <= 0: the column then keeps its state).
+template <int NG, bool MASKED>
+__device__ inline void compute_step(PrefillState (&st)[NG], const uint16_t *sk, const uint16_t *sv,
+                                    const bf16x8 (&qb)[NG][4], float scale_log2e, int valid, int limit,
+                                    int quad, int r) {
+    bf16x8 ka[kStepTiles][4];
+#pragma unroll
+    for (int t = 0; t < kStepTiles; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            ka[t][j] = *reinterpret_cast<const bf16x8 *>(sk + t * kTileElems + r * D + (((4 * j + quad) ^ r) << 3));
+
+    bf16x8 pb[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][j], qb[g][j], s0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][j], qb[g][j], s1, 0, 0, 0);
+        float x[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        if (MASKED) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (4 * quad + i >= limit) x[i] = -INFINITY;
+                if (kTileTokens + 4 * quad + i >= limit) x[4 + i] = -INFINITY;
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = max_over_quads(mx);
+        const float m_new = fmaxf(st[g].m, mx * scale_log2e);
+        const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
+        st[g].m = m_new;
+        float pf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(fmaf(x[i], scale_log2e, -m_new));
+        const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]),
+                          pack_bf16(pf[6], pf[7])};
+        pb[g] = __builtin_bit_cast(bf16x8, pw);
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[g].acc[e] *= alpha;
+            st[g].lsum *= alpha;
+        }
+    }
+
+    uint4 vr[kStepTiles][4];
+#pragma unroll
+    for (int t = 0; t < kStepTiles; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            vr[t][i] = *reinterpret_cast<const uint4 *>(sv + t * kTileElems + (4 * quad + i) * D + 8 * r);
+            if (MASKED && t * kTileTokens + 4 * quad + i >= valid) vr[t][i] = uint4{0u, 0u, 0u, 0u};
+        }
+    const uint32_t v[kStepTiles][4][4] = {
+        {{vr[0][0].x, vr[0][0].y, vr[0][0].z, vr[0][0].w}, {vr[0][1].x, vr[0][1].y, vr[0][1].z, vr[0][1].w},
+         {vr[0][2].x, vr[0][2].y, vr[0][2].z, vr[0][2].w}, {vr[0][3].x, vr[0][3].y, vr[0][3].z, vr[0][3].w}},
+        {{vr[1][0].x, vr[1][0].y, vr[1][0].z, vr[1][0].w}, {vr[1][1].x, vr[1][1].y, vr[1][1].z, vr[1][1].w},
+         {vr[1][2].x, vr[1][2].y, vr[1][2].z, vr[1][2].w}, {vr[1][3].x, vr[1][3].y, vr[1][3].z, vr[1][3].w}}};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        // dword w of a row holds dims 8r+2w (low half) and 8r+2w+1 (high half)
+        const uint4 lo = {__builtin_amdgcn_perm(v[0][1][w], v[0][0][w], 0x05040100u),
+                          __builtin_amdgcn_perm(v[0][3][w], v[0][2][w], 0x05040100u),
+                          __builtin_amdgcn_perm(v[1][1][w], v[1][0][w], 0x05040100u),
+                          __builtin_amdgcn_perm(v[1][3][w], v[1][2][w], 0x05040100u)};
+        const uint4 hi = {__builtin_amdgcn_perm(v[0][1][w], v[0][0][w], 0x07060302u),
+                          __builtin_amdgcn_perm(v[0][3][w], v[0][2][w], 0x07060302u),
+                          __builtin_amdgcn_perm(v[1][1][w], v[1][0][w], 0x07060302u),
+                          __builtin_amdgcn_perm(v[1][3][w], v[1][2][w], 0x07060302u)};
+        const bf16x8 alo = __builtin_bit_cast(bf16x8, lo), ahi = __builtin_bit_cast(bf16x8, hi);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            st[g].acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, pb[g], st[g].acc[2 * w], 0, 0, 0);
+            st[g].acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, pb[g], st[g].acc[2 * w + 1], 0, 0, 0);
+        }
+    }
+    const uint4 one_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, one_bits);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) st[g].lsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[g], st[g].lsum, 0, 0, 0);
+}
 
 template <int NG>
 __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_kernel(
@@ -39,6 +171,8 @@ __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_ker
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
     uint16_t *__restrict__ out, PrefillParams p) {
     __shared__ int s_blk[kMaxPrefillTiles];
+    __shared__ __attribute__((aligned(16))) uint16_t s_k[2][kStepElems];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[2][kStepElems];
 
     // blockIdx.x = head chunk + chunks * (seq + num_seqs * reversed query tile)
     const int chunks = p.num_q_heads / NG;
@@ -52,7 +186,7 @@ __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_ker
     const int S = context_lens[n];
     const int qs = q_start[n];
     const int Qn = q_start[n + 1] - qs;
-    if (qtile * 64 >= Qn || Qn > S) return;
+    if (qtile * 64 >= Qn || Qn > S) return;  // uniform over the workgroup
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -61,24 +195,27 @@ __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_ker
     // stage the block ids of every tile this workgroup can touch
     const int last_pos = S - Qn + min(Qn, qtile * 64 + 64) - 1;
     const int wg_tiles = min((last_pos >> 4) + 1, kMaxPrefillTiles);
+    const int wg_steps = (wg_tiles + kStepTiles - 1) / kStepTiles;
     const int32_t *table = block_tables + size_t(n) * p.max_blocks_per_seq;
     for (int t = tid; t < wg_tiles; t += kThreads) s_blk[t] = table[t >> p.tiles_per_block_log2];
     __syncthreads();
 
+    // wavefronts past the last query row still fetch and synchronise, they just never compute
     const int i0 = qtile * 64 + 16 * wave;  // first query row of this wavefront
-    if (i0 >= Qn) return;
-    const int ncols = min(16, Qn - i0);
+    const bool active = i0 < Qn;
+    const int ncols = active ? min(16, Qn - i0) : 1;
     const int col = min(r, ncols - 1);      // lanes past the last query row shadow it
-    const int p0 = S - Qn + i0;             // position of column 0
+    const int p0 = S - Qn + (active ? i0 : 0);  // position of column 0
     const int my_pos = p0 + col;
-    const int nt = min(((p0 + ncols - 1) >> 4) + 1, wg_tiles);  // tiles 0 .. nt-1
+    const int my_steps = active ? min(((p0 + ncols - 1) / kStepTokens) + 1, wg_steps) : 0;
+    const int free_steps = min((p0 + 1) / kStepTokens, my_steps);  // every token visible to every column
 
     bf16x8 qb[NG][4];
 #pragma unroll
     for (int g = 0; g < NG; ++g)
-        load_q_operand(qb[g], q + (size_t(qs + i0 + col) * p.num_q_heads + head0 + g) * D, quad, true);
+        load_q_operand(qb[g], q + (size_t(qs + (active ? i0 : 0) + col) * p.num_q_heads + head0 + g) * D, quad, true);
 
-    HeadState st[NG];
+    PrefillState st[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) st[g].reset();
 
@@ -86,46 +223,56 @@ __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_ker
     const size_t block_elems = head_elems * p.num_kv_heads;
     const int sub_mask = (1 << p.tiles_per_block_log2) - 1;
 
-    auto issue = [&](uint4(&kr)[4], uint4(&vr)[4], int kt) __attribute__((always_inline)) {
-        const int blk = __builtin_amdgcn_readfirstlane(s_blk[kt]);
-        const size_t base = size_t(blk) * block_elems + size_t(kvh) * head_elems + size_t(kt & sub_mask) * kTileElems;
-        // K/V tiles are re-read by the other wavefronts and head chunks: plain (cached) loads
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kr[j] = *reinterpret_cast<const uint4 *>(k_cache + base + r * D + 32 * j + 8 * quad);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vr[i] = *reinterpret_cast<const uint4 *>(v_cache + base + (4 * quad + i) * D + 8 * r);
+    // this thread's share of a step: 16 bytes of row (tid >> 4), chunk (tid & 15), of each of the
+    // two K tiles and the two V tiles; tiles past the last one re-read it (never used unmasked)
+    const int lrow = tid >> 4, lchunk = tid & 15;
+    const int k_dst = lrow * D + ((lchunk ^ lrow) << 3);
+    const int v_dst = lrow * D + (lchunk << 3);
+    struct Share { uint4 k0, k1, v0, v1; };
+    auto fetch = [&](int step) __attribute__((always_inline)) -> Share {
+        const int t0 = min(step * kStepTiles, wg_tiles - 1), t1 = min(step * kStepTiles + 1, wg_tiles - 1);
+        const size_t in_head = size_t(kvh) * head_elems + lrow * D + (lchunk << 3);
+        const size_t b0 = size_t(s_blk[t0]) * block_elems + size_t(t0 & sub_mask) * kTileElems + in_head;
+        const size_t b1 = size_t(s_blk[t1]) * block_elems + size_t(t1 & sub_mask) * kTileElems + in_head;
+        Share sh;
+        sh.k0 = *reinterpret_cast<const uint4 *>(k_cache + b0);
+        sh.k1 = *reinterpret_cast<const uint4 *>(k_cache + b1);
+        sh.v0 = *reinterpret_cast<const uint4 *>(v_cache + b0);
+        sh.v1 = *reinterpret_cast<const uint4 *>(v_cache + b1);
+        return sh;
     };
-    auto compute = [&](uint4(&kr)[4], uint4(&vr)[4], int kt) __attribute__((always_inline)) {
-        bf16x8 ka[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) ka[j] = __builtin_bit_cast(bf16x8, kr[j]);
-        compute_tile_groups<NG>(st, ka, vr, qb, p.scale_log2e, S - kt * kTileTokens,
-                                my_pos + 1 - kt * kTileTokens, quad);
+    auto park = [&](int stage, const Share &sh) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(&s_k[stage][k_dst]) = sh.k0;
+        *reinterpret_cast<uint4 *>(&s_k[stage][kTileElems + k_dst]) = sh.k1;
+        *reinterpret_cast<uint4 *>(&s_v[stage][v_dst]) = sh.v0;
+        *reinterpret_cast<uint4 *>(&s_v[stage][kTileElems + v_dst]) = sh.v1;
     };
 
-    uint4 kA[4], vA[4], kB[4], vB[4];
-    issue(kA, vA, 0);
-    int kt = 0;
-    for (; kt + 2 < nt; kt += 2) {
-        issue(kB, vB, kt + 1);
-        compute(kA, vA, kt);
-        issue(kA, vA, kt + 2);
-        compute(kB, vB, kt + 1);
-    }
-    if (kt + 1 < nt) {
-        issue(kB, vB, kt + 1);
-        compute(kA, vA, kt);
-        compute(kB, vB, kt + 1);
-    } else {
-        compute(kA, vA, kt);
+    Share next = fetch(0);
+    park(0, next);
+    next = fetch(min(1, wg_steps - 1));
+    __syncthreads();
+    for (int s = 0; s < wg_steps; ++s) {
+        const int stage = s & 1;
+        if (s < free_steps) {
+            compute_step<NG, false>(st, s_k[stage], s_v[stage], qb, p.scale_log2e, kStepTokens, kStepTokens, quad, r);
+        } else if (s < my_steps) {
+            compute_step<NG, true>(st, s_k[stage], s_v[stage], qb, p.scale_log2e, S - s * kStepTokens,
+                                   my_pos + 1 - s * kStepTokens, quad, r);
+        }
+        // the other stage was last read in step s-1, before the barrier that ended it; past the
+        // last step this re-parks and re-fetches the last step (unused) to stay branch free
+        park(stage ^ 1, next);
+        next = fetch(min(s + 2, wg_steps - 1));
+        __syncthreads();
     }
 
+    if (!active) return;
     // lane (quad, r < ncols) holds O[query row i0 + r][head0 + g][32*quad .. +31]
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        st[g].finish();
         if (r < ncols) {
-            const float inv = 1.0f / st[g].l;
+            const float inv = 1.0f / st[g].lsum[0];
             uint16_t *dst = out + (size_t(qs + i0 + r) * p.num_q_heads + head0 + g) * D + 32 * quad;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
