@@ -49,6 +49,7 @@ constexpr int kMaxPrefillTiles = 2048;  // 32768 tokens
 constexpr int kStepTiles = 2;
 constexpr int kStepTokens = kStepTiles * kTileTokens;
 constexpr int kStepElems = kStepTiles * kTileElems;
+constexpr float kLazyLog2 = 8.0f;
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -57,7 +58,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 struct PrefillState {
     floatx4 acc[8];
     floatx4 lsum;  // every entry: running sum of the rounded weights of column r
-    float m;       // running max of the scaled scores (base-2 units) of column r
+    float m;       // reference point of the weights (base-2 units): within 2^kLazyLog2 of the running max of column r
 
     __device__ inline void reset() {
 #pragma unroll
@@ -72,10 +73,12 @@ struct PrefillState {
 __device__ inline float max_over_quads(float x) {
     const unsigned u = __float_as_uint(x);
     const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const float a0 = __uint_as_float(a[0]), a1 = __uint_as_float(a[1]);
+    const float y = a0 > a1 ? a0 : a1;  // inputs are never NaN; a select needs no quieting moves
     const unsigned w = __float_as_uint(y);
     const u32x2 b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    const float b0 = __uint_as_float(b[0]), b1 = __uint_as_float(b[1]);
+    return b0 > b1 ? b0 : b1;
 }
 
 // One 32-token step of NG heads from the K/V rows parked in LDS (sk, sv: [32 tokens][128]).
@@ -101,7 +104,10 @@ __device__ inline void compute_step(PrefillState (&st)[NG], const uint16_t *sk, 
         for (int j = 0; j < 4; ++j) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][j], qb[g][j], s0, 0, 0, 0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][j], qb[g][j], s1, 0, 0, 0);
-        float x[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        // scaled scores; the multiply also leaves canonical values, so the max tree below
+        // compiles to bare v_max3/v_max without one quieting move per input
+        float x[8] = {s0[0] * scale_log2e, s0[1] * scale_log2e, s0[2] * scale_log2e, s0[3] * scale_log2e,
+                      s1[0] * scale_log2e, s1[1] * scale_log2e, s1[2] * scale_log2e, s1[3] * scale_log2e};
         if (MASKED) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -111,20 +117,25 @@ __device__ inline void compute_step(PrefillState (&st)[NG], const uint16_t *sk, 
         }
         float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         mx = max_over_quads(mx);
-        const float m_new = fmaxf(st[g].m, mx * scale_log2e);
-        const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
-        st[g].m = m_new;
-        float pf[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(fmaf(x[i], scale_log2e, -m_new));
-        const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]),
-                          pack_bf16(pf[6], pf[7])};
-        pb[g] = __builtin_bit_cast(bf16x8, pw);
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+        // Lazy rebase: the reference point m only moves when some column's max has grown by more
+        // than 2^kLazyLog2 over it (always in the first step, m = -inf), so weights are at most
+        // 2^kLazyLog2 and the 36 multiplies of the rebase are rare.  Every column has seen token 0
+        // by then, so m - m_new is never inf - inf.
+        if (__builtin_amdgcn_ballot_w64(mx > st[g].m + kLazyLog2) != 0) {
+            const float m_new = fmaxf(st[g].m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
+            st[g].m = m_new;
 #pragma unroll
             for (int e = 0; e < 8; ++e) st[g].acc[e] *= alpha;
             st[g].lsum *= alpha;
         }
+        const float m = st[g].m;
+        float pf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(x[i] - m);
+        const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]),
+                          pack_bf16(pf[6], pf[7])};
+        pb[g] = __builtin_bit_cast(bf16x8, pw);
     }
 
     uint4 vr[kStepTiles][4];
@@ -165,7 +176,7 @@ __device__ inline void compute_step(PrefillState (&st)[NG], const uint16_t *sk, 
 }
 
 template <int NG>
-__global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_kernel(
+__global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
@@ -229,16 +240,19 @@ __global__ __launch_bounds__(kThreads, NG <= 2 ? 2 : 1) void pa_prefill_mfma_ker
     const int k_dst = lrow * D + ((lchunk ^ lrow) << 3);
     const int v_dst = lrow * D + (lchunk << 3);
     struct Share { uint4 k0, k1, v0, v1; };
+    const int lane_off = lrow * D + (lchunk << 3);  // elements inside a tile
+    const uint16_t *k_head = k_cache + size_t(kvh) * head_elems;
+    const uint16_t *v_head = v_cache + size_t(kvh) * head_elems;
     auto fetch = [&](int step) __attribute__((always_inline)) -> Share {
         const int t0 = min(step * kStepTiles, wg_tiles - 1), t1 = min(step * kStepTiles + 1, wg_tiles - 1);
-        const size_t in_head = size_t(kvh) * head_elems + lrow * D + (lchunk << 3);
-        const size_t b0 = size_t(s_blk[t0]) * block_elems + size_t(t0 & sub_mask) * kTileElems + in_head;
-        const size_t b1 = size_t(s_blk[t1]) * block_elems + size_t(t1 & sub_mask) * kTileElems + in_head;
+        // block ids are uniform over the workgroup: tile bases live in scalar registers
+        const size_t b0 = size_t(__builtin_amdgcn_readfirstlane(s_blk[t0])) * block_elems + size_t(t0 & sub_mask) * kTileElems;
+        const size_t b1 = size_t(__builtin_amdgcn_readfirstlane(s_blk[t1])) * block_elems + size_t(t1 & sub_mask) * kTileElems;
         Share sh;
-        sh.k0 = *reinterpret_cast<const uint4 *>(k_cache + b0);
-        sh.k1 = *reinterpret_cast<const uint4 *>(k_cache + b1);
-        sh.v0 = *reinterpret_cast<const uint4 *>(v_cache + b0);
-        sh.v1 = *reinterpret_cast<const uint4 *>(v_cache + b1);
+        sh.k0 = *reinterpret_cast<const uint4 *>(k_head + b0 + lane_off);
+        sh.k1 = *reinterpret_cast<const uint4 *>(k_head + b1 + lane_off);
+        sh.v0 = *reinterpret_cast<const uint4 *>(v_head + b0 + lane_off);
+        sh.v1 = *reinterpret_cast<const uint4 *>(v_head + b1 + lane_off);
         return sh;
     };
     auto park = [&](int stage, const Share &sh) __attribute__((always_inline)) {
