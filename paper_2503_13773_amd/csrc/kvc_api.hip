@@ -373,7 +373,11 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     p.num_q_heads = desc->num_q_heads;
     p.num_kv_heads = desc->num_kv_heads;
     p.group = desc->num_q_heads / desc->num_kv_heads;
+#ifdef KVC_PREFILL_NG
+    p.heads_per_chunk = KVC_PREFILL_NG;
+#else
     p.heads_per_chunk = p.group % 2 == 0 ? 2 : 1;
+#endif
     p.block_size = desc->block_size;
     p.tiles_per_block_log2 = ilog2(desc->block_size / 16);
     p.max_blocks_per_seq = desc->max_blocks_per_seq;

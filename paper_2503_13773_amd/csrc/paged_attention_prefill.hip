@@ -50,11 +50,14 @@ constexpr int kStepTiles = 2;
 constexpr int kStepTokens = kStepTiles * kTileTokens;
 constexpr int kStepElems = kStepTiles * kTileElems;
 constexpr float kLazyLog2 = 8.0f;
+constexpr int kStages = 3;
+constexpr int kVRow = D + 16;                     // padded V row in LDS (288 bytes): see the transpose reads
+constexpr int kVStepElems = kStepTokens * kVRow;
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-// Online-softmax state of one head: 16 query rows (columns r) x 128 dims as in the decode tile
-// code (lane (quad, r) holds O[row r][32*quad .. +31], element 8i + e in acc[e][i]).
+// Online-softmax state of one head: 16 query rows (columns r) x 128 dims; lane (quad, r) holds
+// O[row r][16*e + 4*quad + j] in acc[e][j] (MFMA number e covers dims 16e .. 16e+15).
 struct PrefillState {
     floatx4 acc[8];
     floatx4 lsum;  // every entry: running sum of the rounded weights of column r
@@ -81,98 +84,135 @@ __device__ inline float max_over_quads(float x) {
     return b0 > b1 ? b0 : b1;
 }
 
-// One 32-token step of NG heads from the K/V rows parked in LDS (sk, sv: [32 tokens][128]).
-// MASKED: `valid` = tokens of the step inside the context (wavefront-uniform; V rows past it are
-// zeroed so that NaN stored there cannot reach the output), `limit` = tokens of the step visible
-// to this lane's column (may be <= 0: the column then keeps its state).
-template <int NG, bool MASKED>
-__device__ inline void compute_step(PrefillState (&st)[NG], const uint16_t *sk, const uint16_t *sv,
-                                    const bf16x8 (&qb)[NG][4], float scale_log2e, int valid, int limit,
-                                    int quad, int r) {
+// Scores of one 32-token step: S = K . Q^T for the two 16-token tiles of every head, K rows
+// read from LDS (sk: [32 tokens][128], 16-byte chunks XOR-permuted by the row number).
+template <int NG>
+__device__ inline void step_scores(floatx4 (&s)[NG][kStepTiles], const uint16_t *sk,
+                                   const bf16x8 (&qb)[NG][4], int quad, int r) {
     bf16x8 ka[kStepTiles][4];
 #pragma unroll
     for (int t = 0; t < kStepTiles; ++t)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             ka[t][j] = *reinterpret_cast<const bf16x8 *>(sk + t * kTileElems + r * D + (((4 * j + quad) ^ r) << 3));
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t) {
+            s[g][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[g][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][j], qb[g][j], s[g][t], 0, 0, 0);
+        }
+}
 
+// Scaled (and, if MASKED, causally masked) scores of one head and their max over the step's
+// tokens.  The multiply also leaves canonical values, so the max tree compiles to bare
+// v_max3/v_max without one quieting move per input.  `limit` = tokens of the step visible to
+// this lane's column (may be <= 0).
+template <bool MASKED>
+__device__ inline float scale_mask_max(float (&x)[8], const floatx4 (&s)[kStepTiles], float scale_log2e,
+                                       int limit, int quad) {
+#pragma unroll
+    for (int t = 0; t < kStepTiles; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[4 * t + i] = s[t][i] * scale_log2e;
+            if (MASKED && t * kTileTokens + 4 * quad + i >= limit) x[4 * t + i] = -INFINITY;
+        }
+    const float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    return max_over_quads(mx);
+}
+
+// Lazy rebase: the reference point m only moves when some column's max has grown by more than
+// 2^kLazyLog2 over it (always in the first step, m = -inf), so weights are at most 2^kLazyLog2
+// and the 36 multiplies of the rebase are rare.  Every column sees token 0 in its first step,
+// so m - m_new is never inf - inf.
+__device__ inline void rebase(PrefillState &st, float mx) {
+    if (__builtin_amdgcn_ballot_w64(mx > st.m + kLazyLog2) != 0) {
+        const float m_new = fmaxf(st.m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+        st.m = m_new;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.acc[e] *= alpha;
+        st.lsum *= alpha;
+    }
+}
+
+// One turn of the software pipeline: the weights and the P.V accumulation of step `cur` (scaled
+// scores in x, V rows in sv_cur) together with the scores, scaling and max of step `next` (K rows
+// in sk_next), in one straight-line region so that the matrix-core work of one step runs under
+// the vector work of the other.  On return x holds the scaled scores of step `next` and the
+// reference points are rebased for it.
+// MASKED: `vlim_cur` = tokens of step cur visible to any column of this wavefront (V rows past
+// it are zeroed: their weights are zero for every column and the rows may hold NaN);
+// `limit_next` = tokens of step next visible to this lane's column.
+template <int NG, bool MASKED>
+__device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], const uint16_t *sk_next,
+                                     const uint16_t *sv_cur, const bf16x8 (&qb)[NG][4], float scale_log2e,
+                                     int vlim_cur, int limit_next, int quad, int r) {
+    // A operands of O^T += V^T . P^T straight from LDS: the transpose read hands lane i of a
+    // 16-lane block the i-th 16-bit element of each of the four 16-element groups that lanes
+    // 4k .. 4k+3 of the block point at (8 bytes each).  Lanes 4k .. 4k+3 of block `quad` point at
+    // dims 16e + 0, 4, 8, 12 of token 4*quad + k, so lane r receives dim 16e + r of tokens
+    // 4*quad .. +3: the depth slots in the order the score layout fixed.
+    typedef short v4i16 __attribute__((ext_vector_type(4)));
+    typedef v4i16 __attribute__((address_space(3))) * lds_v4i16_ptr;
+    const uint16_t *vlane = sv_cur + (4 * quad + (r >> 2)) * kVRow + 4 * (r & 3);
+    uint2 va[8][kStepTiles];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t)
+            va[e][t] = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                     (lds_v4i16_ptr)(vlane + t * kTileTokens * kVRow + 16 * e)));
+    if (MASKED) {
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t) {
+            const int tok = t * kTileTokens + 4 * quad;
+            const uint32_t m01 = (tok < vlim_cur ? 0xffffu : 0u) | (tok + 1 < vlim_cur ? 0xffff0000u : 0u);
+            const uint32_t m23 = (tok + 2 < vlim_cur ? 0xffffu : 0u) | (tok + 3 < vlim_cur ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                va[e][t].x &= m01;
+                va[e][t].y &= m23;
+            }
+        }
+    }
+
+    floatx4 s[NG][kStepTiles];
+    step_scores<NG>(s, sk_next, qb, quad, r);
+
+    // weights of step cur, rounded to bf16: the B operand of P.V as they stand
     bf16x8 pb[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][j], qb[g][j], s0, 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][j], qb[g][j], s1, 0, 0, 0);
-        // scaled scores; the multiply also leaves canonical values, so the max tree below
-        // compiles to bare v_max3/v_max without one quieting move per input
-        float x[8] = {s0[0] * scale_log2e, s0[1] * scale_log2e, s0[2] * scale_log2e, s0[3] * scale_log2e,
-                      s1[0] * scale_log2e, s1[1] * scale_log2e, s1[2] * scale_log2e, s1[3] * scale_log2e};
-        if (MASKED) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (4 * quad + i >= limit) x[i] = -INFINITY;
-                if (kTileTokens + 4 * quad + i >= limit) x[4 + i] = -INFINITY;
-            }
-        }
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        mx = max_over_quads(mx);
-        // Lazy rebase: the reference point m only moves when some column's max has grown by more
-        // than 2^kLazyLog2 over it (always in the first step, m = -inf), so weights are at most
-        // 2^kLazyLog2 and the 36 multiplies of the rebase are rare.  Every column has seen token 0
-        // by then, so m - m_new is never inf - inf.
-        if (__builtin_amdgcn_ballot_w64(mx > st[g].m + kLazyLog2) != 0) {
-            const float m_new = fmaxf(st[g].m, mx);
-            const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
-            st[g].m = m_new;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) st[g].acc[e] *= alpha;
-            st[g].lsum *= alpha;
-        }
         const float m = st[g].m;
         float pf[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(x[i] - m);
+        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(x[g][i] - m);
         const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]),
                           pack_bf16(pf[6], pf[7])};
         pb[g] = __builtin_bit_cast(bf16x8, pw);
     }
 
-    uint4 vr[kStepTiles][4];
 #pragma unroll
-    for (int t = 0; t < kStepTiles; ++t)
+    for (int e = 0; e < 8; ++e) {
+        const uint4 aw = {va[e][0].x, va[e][0].y, va[e][1].x, va[e][1].y};
+        const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            vr[t][i] = *reinterpret_cast<const uint4 *>(sv + t * kTileElems + (4 * quad + i) * D + 8 * r);
-            if (MASKED && t * kTileTokens + 4 * quad + i >= valid) vr[t][i] = uint4{0u, 0u, 0u, 0u};
-        }
-    const uint32_t v[kStepTiles][4][4] = {
-        {{vr[0][0].x, vr[0][0].y, vr[0][0].z, vr[0][0].w}, {vr[0][1].x, vr[0][1].y, vr[0][1].z, vr[0][1].w},
-         {vr[0][2].x, vr[0][2].y, vr[0][2].z, vr[0][2].w}, {vr[0][3].x, vr[0][3].y, vr[0][3].z, vr[0][3].w}},
-        {{vr[1][0].x, vr[1][0].y, vr[1][0].z, vr[1][0].w}, {vr[1][1].x, vr[1][1].y, vr[1][1].z, vr[1][1].w},
-         {vr[1][2].x, vr[1][2].y, vr[1][2].z, vr[1][2].w}, {vr[1][3].x, vr[1][3].y, vr[1][3].z, vr[1][3].w}}};
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        // dword w of a row holds dims 8r+2w (low half) and 8r+2w+1 (high half)
-        const uint4 lo = {__builtin_amdgcn_perm(v[0][1][w], v[0][0][w], 0x05040100u),
-                          __builtin_amdgcn_perm(v[0][3][w], v[0][2][w], 0x05040100u),
-                          __builtin_amdgcn_perm(v[1][1][w], v[1][0][w], 0x05040100u),
-                          __builtin_amdgcn_perm(v[1][3][w], v[1][2][w], 0x05040100u)};
-        const uint4 hi = {__builtin_amdgcn_perm(v[0][1][w], v[0][0][w], 0x07060302u),
-                          __builtin_amdgcn_perm(v[0][3][w], v[0][2][w], 0x07060302u),
-                          __builtin_amdgcn_perm(v[1][1][w], v[1][0][w], 0x07060302u),
-                          __builtin_amdgcn_perm(v[1][3][w], v[1][2][w], 0x07060302u)};
-        const bf16x8 alo = __builtin_bit_cast(bf16x8, lo), ahi = __builtin_bit_cast(bf16x8, hi);
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            st[g].acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, pb[g], st[g].acc[2 * w], 0, 0, 0);
-            st[g].acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, pb[g], st[g].acc[2 * w + 1], 0, 0, 0);
-        }
+        for (int g = 0; g < NG; ++g)
+            st[g].acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[g], st[g].acc[e], 0, 0, 0);
     }
     const uint4 one_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
     const bf16x8 ones = __builtin_bit_cast(bf16x8, one_bits);
 #pragma unroll
     for (int g = 0; g < NG; ++g) st[g].lsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[g], st[g].lsum, 0, 0, 0);
+
+    float mx[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) mx[g] = scale_mask_max<MASKED>(x[g], s[g], scale_log2e, limit_next, quad);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) rebase(st[g], mx[g]);
 }
 
 template <int NG>
@@ -182,8 +222,8 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
     uint16_t *__restrict__ out, PrefillParams p) {
     __shared__ int s_blk[kMaxPrefillTiles];
-    __shared__ __attribute__((aligned(16))) uint16_t s_k[2][kStepElems];
-    __shared__ __attribute__((aligned(16))) uint16_t s_v[2][kStepElems];
+    __shared__ __attribute__((aligned(16))) uint16_t s_k[kStages][kStepElems];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[kStages][kVStepElems];
 
     // blockIdx.x = head chunk + chunks * (seq + num_seqs * reversed query tile)
     const int chunks = p.num_q_heads / NG;
@@ -218,8 +258,8 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     const int col = min(r, ncols - 1);      // lanes past the last query row shadow it
     const int p0 = S - Qn + (active ? i0 : 0);  // position of column 0
     const int my_pos = p0 + col;
-    const int my_steps = active ? min(((p0 + ncols - 1) / kStepTokens) + 1, wg_steps) : 0;
-    const int free_steps = min((p0 + 1) / kStepTokens, my_steps);  // every token visible to every column
+    const int wave_vis = p0 + ncols;        // tokens visible to some column of this wavefront
+    const int free_steps = (p0 + 1) / kStepTokens;  // steps whose every token every column sees
 
     bf16x8 qb[NG][4];
 #pragma unroll
@@ -238,7 +278,7 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     // two K tiles and the two V tiles; tiles past the last one re-read it (never used unmasked)
     const int lrow = tid >> 4, lchunk = tid & 15;
     const int k_dst = lrow * D + ((lchunk ^ lrow) << 3);
-    const int v_dst = lrow * D + (lchunk << 3);
+    const int v_dst = lrow * kVRow + (lchunk << 3);
     struct Share { uint4 k0, k1, v0, v1; };
     const int lane_off = lrow * D + (lchunk << 3);  // elements inside a tile
     const uint16_t *k_head = k_cache + size_t(kvh) * head_elems;
@@ -259,43 +299,58 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
         *reinterpret_cast<uint4 *>(&s_k[stage][k_dst]) = sh.k0;
         *reinterpret_cast<uint4 *>(&s_k[stage][kTileElems + k_dst]) = sh.k1;
         *reinterpret_cast<uint4 *>(&s_v[stage][v_dst]) = sh.v0;
-        *reinterpret_cast<uint4 *>(&s_v[stage][kTileElems + v_dst]) = sh.v1;
+        *reinterpret_cast<uint4 *>(&s_v[stage][kTileTokens * kVRow + v_dst]) = sh.v1;
     };
 
+    // Step s lives in stage s % 3.  Turn s reads the K rows of step s+1 and the V rows of step
+    // s, then parks step s+2 (fetched during turn s-1) over step s-1, whose last reader passed
+    // the barrier that ended turn s-1, and fetches step s+3.  Past the last step the last one
+    // is fetched and parked again (unused) to keep the loop branch free.
     Share next = fetch(0);
     park(0, next);
     next = fetch(min(1, wg_steps - 1));
+    park(1, next);
+    next = fetch(min(2, wg_steps - 1));
     __syncthreads();
+
+    float x[NG][8];
+    if (active) {  // scores of step 0
+        floatx4 s[NG][kStepTiles];
+        step_scores<NG>(s, s_k[0], qb, quad, r);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) rebase(st[g], scale_mask_max<true>(x[g], s[g], p.scale_log2e, my_pos + 1, quad));
+    }
+    int cur = 0, nxt = 1, wr = 2;
     for (int s = 0; s < wg_steps; ++s) {
-        const int stage = s & 1;
-        if (s < free_steps) {
-            compute_step<NG, false>(st, s_k[stage], s_v[stage], qb, p.scale_log2e, kStepTokens, kStepTokens, quad, r);
-        } else if (s < my_steps) {
-            compute_step<NG, true>(st, s_k[stage], s_v[stage], qb, p.scale_log2e, S - s * kStepTokens,
-                                   my_pos + 1 - s * kStepTokens, quad, r);
+        if (active) {
+            if (s + 1 < free_steps)
+                pipeline_turn<NG, false>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, kStepTokens, kStepTokens, quad, r);
+            else
+                pipeline_turn<NG, true>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, wave_vis - s * kStepTokens,
+                                        my_pos + 1 - (s + 1) * kStepTokens, quad, r);
         }
-        // the other stage was last read in step s-1, before the barrier that ended it; past the
-        // last step this re-parks and re-fetches the last step (unused) to stay branch free
-        park(stage ^ 1, next);
-        next = fetch(min(s + 2, wg_steps - 1));
+        park(wr, next);
+        next = fetch(min(s + 3, wg_steps - 1));
         __syncthreads();
+        const int t = cur;
+        cur = nxt;
+        nxt = wr;
+        wr = t;
     }
 
     if (!active) return;
-    // lane (quad, r < ncols) holds O[query row i0 + r][head0 + g][32*quad .. +31]
+    // lane (quad, r < ncols) holds O[query row i0 + r][head0 + g][16*e + 4*quad .. +3] in acc[e]
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         if (r < ncols) {
             const float inv = 1.0f / st[g].lsum[0];
-            uint16_t *dst = out + (size_t(qs + i0 + r) * p.num_q_heads + head0 + g) * D + 32 * quad;
+            uint16_t *dst = out + (size_t(qs + i0 + r) * p.num_q_heads + head0 + g) * D + 4 * quad;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint4 w;
-                w.x = pack_bf16(st[g].acc[0][i] * inv, st[g].acc[1][i] * inv);
-                w.y = pack_bf16(st[g].acc[2][i] * inv, st[g].acc[3][i] * inv);
-                w.z = pack_bf16(st[g].acc[4][i] * inv, st[g].acc[5][i] * inv);
-                w.w = pack_bf16(st[g].acc[6][i] * inv, st[g].acc[7][i] * inv);
-                *reinterpret_cast<uint4 *>(dst + 8 * i) = w;
+            for (int e = 0; e < 8; ++e) {
+                uint2 w;
+                w.x = pack_bf16(st[g].acc[e][0] * inv, st[g].acc[e][1] * inv);
+                w.y = pack_bf16(st[g].acc[e][2] * inv, st[g].acc[e][3] * inv);
+                *reinterpret_cast<uint2 *>(dst + 16 * e) = w;
             }
         }
     }
