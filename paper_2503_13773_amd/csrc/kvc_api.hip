@@ -362,8 +362,7 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     int rc = make_plan(desc, &pl);
     if (rc != KVC_OK) return rc;
     if (total_q < 0 || max_query_len < 0) return KVC_ERR_BAD_SHAPE;
-    if (!mfma_ok(*desc) || int64_t(desc->max_blocks_per_seq) * desc->block_size > 32768)
-        return KVC_ERR_UNSUPPORTED;
+    if (!mfma_ok(*desc)) return KVC_ERR_UNSUPPORTED;
     if (desc->num_seqs == 0 || total_q == 0 || max_query_len == 0) return KVC_OK;
     if (!q_start) return KVC_ERR_NULL;
     rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
@@ -373,11 +372,7 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     p.num_q_heads = desc->num_q_heads;
     p.num_kv_heads = desc->num_kv_heads;
     p.group = desc->num_q_heads / desc->num_kv_heads;
-#ifdef KVC_PREFILL_NG
-    p.heads_per_chunk = KVC_PREFILL_NG;
-#else
     p.heads_per_chunk = p.group % 2 == 0 ? 2 : 1;
-#endif
     p.block_size = desc->block_size;
     p.tiles_per_block_log2 = ilog2(desc->block_size / 16);
     p.max_blocks_per_seq = desc->max_blocks_per_seq;

@@ -31,7 +31,7 @@ struct PrefillParams {
     int num_q_heads;
     int num_kv_heads;
     int group;                 // num_q_heads / num_kv_heads
-    int heads_per_chunk;       // query heads one wavefront carries (1, 2 or 4; divides group)
+    int heads_per_chunk;       // query heads one wavefront carries (1 or 2; divides group)
     int block_size;
     int tiles_per_block_log2;  // log2(block_size / 16)
     int max_blocks_per_seq;

@@ -32,8 +32,7 @@
 // below the diagonal of all 16 rows run code without mask or range checks.  Token 0 is visible
 // to every query row and steps are walked in order, so every column has a finite running max
 // after the first step.  Workgroups with the most steps (the last query rows) are dispatched
-// first.  The block ids of the sequence are staged in LDS once per workgroup (contexts up to
-// 32768 tokens).
+// first.
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -45,7 +44,6 @@ namespace {
 
 using namespace mfma;
 
-constexpr int kMaxPrefillTiles = 2048;  // 32768 tokens
 constexpr int kStepTiles = 2;
 constexpr int kStepTokens = kStepTiles * kTileTokens;
 constexpr int kStepElems = kStepTiles * kTileElems;
@@ -216,12 +214,11 @@ __device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], 
 }
 
 template <int NG>
-__global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_prefill_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
     uint16_t *__restrict__ out, PrefillParams p) {
-    __shared__ int s_blk[kMaxPrefillTiles];
     __shared__ __attribute__((aligned(16))) uint16_t s_k[kStages][kStepElems];
     __shared__ __attribute__((aligned(16))) uint16_t s_v[kStages][kVStepElems];
 
@@ -243,13 +240,11 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     const int wave = tid >> 6, lane = tid & 63;
     const int quad = lane >> 4, r = lane & 15;
 
-    // stage the block ids of every tile this workgroup can touch
+    // tiles and steps this workgroup walks (up to the position of its last query row)
     const int last_pos = S - Qn + min(Qn, qtile * 64 + 64) - 1;
-    const int wg_tiles = min((last_pos >> 4) + 1, kMaxPrefillTiles);
+    const int wg_tiles = (last_pos >> 4) + 1;
     const int wg_steps = (wg_tiles + kStepTiles - 1) / kStepTiles;
     const int32_t *table = block_tables + size_t(n) * p.max_blocks_per_seq;
-    for (int t = tid; t < wg_tiles; t += kThreads) s_blk[t] = table[t >> p.tiles_per_block_log2];
-    __syncthreads();
 
     // wavefronts past the last query row still fetch and synchronise, they just never compute
     const int i0 = qtile * 64 + 16 * wave;  // first query row of this wavefront
@@ -283,11 +278,21 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     const int lane_off = lrow * D + (lchunk << 3);  // elements inside a tile
     const uint16_t *k_head = k_cache + size_t(kvh) * head_elems;
     const uint16_t *v_head = v_cache + size_t(kvh) * head_elems;
-    auto fetch = [&](int step) __attribute__((always_inline)) -> Share {
-        const int t0 = min(step * kStepTiles, wg_tiles - 1), t1 = min(step * kStepTiles + 1, wg_tiles - 1);
-        // block ids are uniform over the workgroup: tile bases live in scalar registers
-        const size_t b0 = size_t(__builtin_amdgcn_readfirstlane(s_blk[t0])) * block_elems + size_t(t0 & sub_mask) * kTileElems;
-        const size_t b1 = size_t(__builtin_amdgcn_readfirstlane(s_blk[t1])) * block_elems + size_t(t1 & sub_mask) * kTileElems;
+    // Block ids are uniform over the workgroup: they come through the scalar cache, one turn
+    // before the fetch that uses them, and the tile bases live in scalar registers.  Tiles past
+    // the last one repeat it (never used unmasked).
+    struct Ids { int t0, t1, b0, b1; };
+    auto ids_of = [&](int step) __attribute__((always_inline)) -> Ids {
+        Ids id;
+        id.t0 = min(step * kStepTiles, wg_tiles - 1);
+        id.t1 = min(step * kStepTiles + 1, wg_tiles - 1);
+        id.b0 = __builtin_amdgcn_readfirstlane(table[id.t0 >> p.tiles_per_block_log2]);
+        id.b1 = __builtin_amdgcn_readfirstlane(table[id.t1 >> p.tiles_per_block_log2]);
+        return id;
+    };
+    auto fetch = [&](const Ids &id) __attribute__((always_inline)) -> Share {
+        const size_t b0 = size_t(id.b0) * block_elems + size_t(id.t0 & sub_mask) * kTileElems;
+        const size_t b1 = size_t(id.b1) * block_elems + size_t(id.t1 & sub_mask) * kTileElems;
         Share sh;
         sh.k0 = *reinterpret_cast<const uint4 *>(k_head + b0 + lane_off);
         sh.k1 = *reinterpret_cast<const uint4 *>(k_head + b1 + lane_off);
@@ -302,15 +307,17 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
         *reinterpret_cast<uint4 *>(&s_v[stage][kTileTokens * kVRow + v_dst]) = sh.v1;
     };
 
-    // Step s lives in stage s % 3.  Turn s reads the K rows of step s+1 and the V rows of step
-    // s, then parks step s+2 (fetched during turn s-1) over step s-1, whose last reader passed
-    // the barrier that ended turn s-1, and fetches step s+3.  Past the last step the last one
-    // is fetched and parked again (unused) to keep the loop branch free.
-    Share next = fetch(0);
+    // Step s lives in stage s % 3.  Turn s first parks step s+2 (fetched during turn s-1) over
+    // step s-1, whose last reader passed the barrier that ended turn s-1, and issues the fetch of
+    // step s+3; then it reads the K rows of step s+1 and the V rows of step s.  The barrier at its
+    // end publishes step s+2 for turn s+1.  Past the last step the last one is fetched and parked
+    // again (unused) to keep the loop branch free.
+    Share next = fetch(ids_of(0));
     park(0, next);
-    next = fetch(min(1, wg_steps - 1));
+    next = fetch(ids_of(min(1, wg_steps - 1)));
     park(1, next);
-    next = fetch(min(2, wg_steps - 1));
+    next = fetch(ids_of(min(2, wg_steps - 1)));
+    Ids ids = ids_of(min(3, wg_steps - 1));
     __syncthreads();
 
     float x[NG][8];
@@ -322,6 +329,9 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
     }
     int cur = 0, nxt = 1, wr = 2;
     for (int s = 0; s < wg_steps; ++s) {
+        park(wr, next);
+        next = fetch(ids);
+        ids = ids_of(min(s + 4, wg_steps - 1));
         if (active) {
             if (s + 1 < free_steps)
                 pipeline_turn<NG, false>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, kStepTokens, kStepTokens, quad, r);
@@ -329,8 +339,6 @@ __global__ __launch_bounds__(kThreads, NG == 1 ? 3 : NG == 2 ? 2 : 1) void pa_pr
                 pipeline_turn<NG, true>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, wave_vis - s * kStepTokens,
                                         my_pos + 1 - (s + 1) * kStepTokens, quad, r);
         }
-        park(wr, next);
-        next = fetch(min(s + 3, wg_steps - 1));
         __syncthreads();
         const int t = cur;
         cur = nxt;
@@ -369,8 +377,7 @@ hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v
     const int ng = p.heads_per_chunk;
     const unsigned grid = unsigned(int64_t(p.num_q_heads / ng) * p.num_seqs * p.max_query_tiles);
     const dim3 g(grid), b(kThreads);
-    if (ng == 4) pa_prefill_mfma_kernel<4><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
-    else if (ng == 2) pa_prefill_mfma_kernel<2><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    if (ng == 2) pa_prefill_mfma_kernel<2><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
     else pa_prefill_mfma_kernel<1><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
     return hipGetLastError();
 }

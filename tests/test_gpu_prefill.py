@@ -113,3 +113,33 @@ def test_prefill_argument_errors():
     w, q, qs = make(340, [20], [20], 4, 2, bs=8)
     with pytest.raises(K.KvcError):                      # block_size 8 is not on this path
         run(w, q, qs, 20)
+
+
+def test_context_beyond_32k_tokens_chunk(oracle_mod):
+    """The last 150 positions of a 40000-token context (block ids come through the scalar cache,
+    no per-workgroup table staging, so the context length is not bounded by LDS)."""
+    w, q, qs = make(350, [40000, 33], [150, 33], 4, 2)
+    check(oracle_mod, w, q, qs, "40000-token context")
+
+
+def test_scores_that_keep_growing_along_the_context(oracle_mod):
+    """Scores that rise steadily with the token index keep the running max moving by a few units
+    (base 2) per 32-token step, and large queries give a wide dynamic range: both the rare
+    full rebase of the softmax reference point and the steps in between are exercised."""
+    rng = np.random.default_rng(360)
+    lens = [700, 257]
+    w, q, qs = make(360, lens, lens, 4, 2)
+    kf = W.bf16_bits_to_f32(w.k_cache).copy()
+    u = rng.standard_normal(128).astype(np.float32)
+    u /= np.linalg.norm(u)
+    nblk = W.blocks_needed(w.context_lens, 16)
+    for n, L in enumerate(lens):
+        for b in range(nblk[n]):
+            t = (16 * b + np.arange(16)).astype(np.float32)
+            kf[w.block_tables[n, b]] += (0.12 * t)[None, :, None] * u[None, None, :] * np.sqrt(128.0)
+    w.k_cache[...] = W.f32_to_bf16_bits(kf)
+    qf = W.bf16_bits_to_f32(q) * 0.3 + u[None, None, :] * 1.0
+    q = W.f32_to_bf16_bits(qf.astype(np.float32))
+    check(oracle_mod, w, q, qs, "rising scores")
+    q = W.f32_to_bf16_bits((W.bf16_bits_to_f32(q) * 6.0).astype(np.float32))
+    check(oracle_mod, w, q, qs, "rising scores, 6x queries")
