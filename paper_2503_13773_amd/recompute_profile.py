@@ -41,7 +41,8 @@ def causal_attention_flops(S: int, q_heads: int, head_dim: int) -> float:
 
 
 def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int = 32, kv_heads: int = 8,
-                      head_dim: int = 128, block_size: int = 16, reps: int = 5, seed: int = 0) -> Dict:
+                      head_dim: int = 128, block_size: int = 16, reps: int = 5, seed: int = 0,
+                      fit_from: int = 2048) -> Dict:
     import torch
 
     from . import binding as K
@@ -73,9 +74,27 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
         fl = causal_attention_flops(S, q_heads, head_dim)
         samples.append({"S": int(S), "layer_ms": ms, "all_layers_ms": ms * layers,
                         "tflops": fl / ms / 1e9, "frac_of_mfma_peak": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS})
-    alpha, beta = fit_power_law([s["S"] for s in samples], [s["all_layers_ms"] for s in samples])
-    return {"model": {"layers": layers, "q_heads": q_heads, "kv_heads": kv_heads, "head_dim": head_dim,
+    fit = [s for s in samples if s["S"] >= fit_from] if sum(s["S"] >= fit_from for s in samples) >= 2 else samples
+    alpha, beta = fit_power_law([s["S"] for s in fit], [s["all_layers_ms"] for s in fit])
+    return {"fit_from": fit_from, "model": {"layers": layers, "q_heads": q_heads, "kv_heads": kv_heads, "head_dim": head_dim,
                       "block_size": block_size}, "samples": samples, "alpha_ms": alpha, "beta": beta}
+
+
+def markdown(res: Dict, swap_gamma_ms: float, swap_delta_ms: float) -> str:
+    """The table, the fit and the crossover with the swap regressor L_s = gamma * S + delta."""
+    from . import policy
+
+    m = res["model"]
+    lines = ["| S tokens | per layer ms | all %d layers ms | TFLOP/s | %% of MFMA peak |" % m["layers"], "|---|---|---|---|---|"]
+    for s in res["samples"]:
+        lines.append("| %d | %.3f | %.2f | %.1f | %.1f |" % (s["S"], s["layer_ms"], s["all_layers_ms"], s["tflops"],
+                                                           100 * s["frac_of_mfma_peak"]))
+    lines.append("")
+    lines.append("Power-law fit over S >= %d (all layers): L_r(S) = %.4g ms * S^%.3f." % (res["fit_from"], res["alpha_ms"],
+                                                                                         res["beta"]))
+    ss = policy.sweet_spot(swap_gamma_ms, swap_delta_ms, res["alpha_ms"], res["beta"], 0.0, 0.0, 1e6)
+    lines.append("Against L_s(S) = %.6g ms * S + %.4g ms the two meet at S_s = %.0f tokens." % (swap_gamma_ms, swap_delta_ms, ss))
+    return "\n".join(lines)
 
 
 def main() -> int:
@@ -85,9 +104,13 @@ def main() -> int:
     ap.add_argument("--kv-heads", type=int, default=8)
     ap.add_argument("--seq-lens", type=int, nargs="+", default=[256, 512, 1024, 2048, 4096, 8192, 16384])
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--markdown", action="store_true", help="print a table instead of JSON")
+    ap.add_argument("--swap-gamma-ms", type=float, default=0.004744, help="slope of the swap regressor (ms per token)")
+    ap.add_argument("--swap-delta-ms", type=float, default=0.145, help="offset of the swap regressor (ms)")
     args = ap.parse_args()
-    print(json.dumps(profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads,
-                                       kv_heads=args.kv_heads, reps=args.reps)))
+    res = profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads, kv_heads=args.kv_heads,
+                            reps=args.reps)
+    print(markdown(res, args.swap_gamma_ms, args.swap_delta_ms) if args.markdown else json.dumps(res))
     return 0
 
 
