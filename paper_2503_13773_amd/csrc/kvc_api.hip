@@ -362,7 +362,8 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     int rc = make_plan(desc, &pl);
     if (rc != KVC_OK) return rc;
     if (total_q < 0 || max_query_len < 0) return KVC_ERR_BAD_SHAPE;
-    if (!mfma_ok(*desc)) return KVC_ERR_UNSUPPORTED;
+    if (desc->dtype != KVC_BF16 || desc->head_dim != 128 || desc->num_q_heads / desc->num_kv_heads > 16)
+        return KVC_ERR_UNSUPPORTED;
     if (desc->num_seqs == 0 || total_q == 0 || max_query_len == 0) return KVC_OK;
     if (!q_start) return KVC_ERR_NULL;
     rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
@@ -374,7 +375,8 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     p.group = desc->num_q_heads / desc->num_kv_heads;
     p.heads_per_chunk = p.group % 2 == 0 ? 2 : 1;
     p.block_size = desc->block_size;
-    p.tiles_per_block_log2 = ilog2(desc->block_size / 16);
+    p.block_size_log2 = ilog2(desc->block_size);
+    p.tiles_per_block_log2 = desc->block_size >= 16 ? ilog2(desc->block_size / 16) : 0;
     p.max_blocks_per_seq = desc->max_blocks_per_seq;
     p.max_query_tiles = int(ceil_div(max_query_len, 64));
     p.scale_log2e = float(double(scale) * 1.4426950408889634);

@@ -33,7 +33,8 @@ struct PrefillParams {
     int group;                 // num_q_heads / num_kv_heads
     int heads_per_chunk;       // query heads one wavefront carries (1 or 2; divides group)
     int block_size;
-    int tiles_per_block_log2;  // log2(block_size / 16)
+    int block_size_log2;
+    int tiles_per_block_log2;  // log2(block_size / 16); 0 for block sizes below 16
     int max_blocks_per_seq;
     int max_query_tiles;       // ceil(max_query_len / 64)
     float scale_log2e;

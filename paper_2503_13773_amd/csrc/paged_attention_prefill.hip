@@ -1,5 +1,5 @@
 // Causal attention of many query positions per sequence over the block-allocated KV cache on
-// the matrix cores (gfx950, bf16, head_dim 128, block_size a multiple of 16): the recomputation
+// the matrix cores (gfx950, bf16, head_dim 128, any power-of-two block_size): the recomputation
 // path of a preempted request (prefill re-run over prompt + generated tokens, quadratic in the
 // sequence length: paper Section 2.5 and 3.5) and chunked prefill.
 //
@@ -33,6 +33,12 @@
 // to every query row and steps are walked in order, so every column has a finite running max
 // after the first step.  Workgroups with the most steps (the last query rows) are dispatched
 // first.
+//
+// Block sizes below 16 (SMALL): a 16-token tile spans several blocks, so every thread looks up
+// the block of the one row it fetches (its table entry comes one turn ahead, like the scalar
+// ids of the large-block path); rows past the workgroup's last needed token re-read that token
+// (their blocks may not be allocated), they are masked and their V rows zeroed like any row past
+// the diagonal.
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -213,7 +219,7 @@ __device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], 
     for (int g = 0; g < NG; ++g) rebase(st[g], mx[g]);
 }
 
-template <int NG>
+template <int NG, bool SMALL>
 __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
@@ -278,26 +284,42 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma_kernel(
     const int lane_off = lrow * D + (lchunk << 3);  // elements inside a tile
     const uint16_t *k_head = k_cache + size_t(kvh) * head_elems;
     const uint16_t *v_head = v_cache + size_t(kvh) * head_elems;
-    // Block ids are uniform over the workgroup: they come through the scalar cache, one turn
-    // before the fetch that uses them, and the tile bases live in scalar registers.  Tiles past
-    // the last one repeat it (never used unmasked).
+    // Large blocks: block ids are uniform over the workgroup, they come through the scalar cache
+    // one turn before the fetch that uses them, and the tile bases live in scalar registers.
+    // Tiles past the last one repeat it (never used unmasked).  Small blocks: b0 / b1 are the
+    // blocks of this thread's row in the two tiles, t0 / t1 the row's slot inside its block.
     struct Ids { int t0, t1, b0, b1; };
     auto ids_of = [&](int step) __attribute__((always_inline)) -> Ids {
         Ids id;
-        id.t0 = min(step * kStepTiles, wg_tiles - 1);
-        id.t1 = min(step * kStepTiles + 1, wg_tiles - 1);
-        id.b0 = __builtin_amdgcn_readfirstlane(table[id.t0 >> p.tiles_per_block_log2]);
-        id.b1 = __builtin_amdgcn_readfirstlane(table[id.t1 >> p.tiles_per_block_log2]);
+        if (SMALL) {
+            const int tok0 = min(step * kStepTokens + lrow, last_pos);
+            const int tok1 = min(step * kStepTokens + kTileTokens + lrow, last_pos);
+            id.t0 = tok0 & (p.block_size - 1);
+            id.t1 = tok1 & (p.block_size - 1);
+            id.b0 = table[tok0 >> p.block_size_log2];
+            id.b1 = table[tok1 >> p.block_size_log2];
+        } else {
+            id.t0 = min(step * kStepTiles, wg_tiles - 1);
+            id.t1 = min(step * kStepTiles + 1, wg_tiles - 1);
+            id.b0 = __builtin_amdgcn_readfirstlane(table[id.t0 >> p.tiles_per_block_log2]);
+            id.b1 = __builtin_amdgcn_readfirstlane(table[id.t1 >> p.tiles_per_block_log2]);
+        }
         return id;
     };
     auto fetch = [&](const Ids &id) __attribute__((always_inline)) -> Share {
-        const size_t b0 = size_t(id.b0) * block_elems + size_t(id.t0 & sub_mask) * kTileElems;
-        const size_t b1 = size_t(id.b1) * block_elems + size_t(id.t1 & sub_mask) * kTileElems;
+        size_t b0, b1;
+        if (SMALL) {
+            b0 = size_t(id.b0) * block_elems + size_t(id.t0) * D + (lchunk << 3);
+            b1 = size_t(id.b1) * block_elems + size_t(id.t1) * D + (lchunk << 3);
+        } else {
+            b0 = size_t(id.b0) * block_elems + size_t(id.t0 & sub_mask) * kTileElems + lane_off;
+            b1 = size_t(id.b1) * block_elems + size_t(id.t1 & sub_mask) * kTileElems + lane_off;
+        }
         Share sh;
-        sh.k0 = *reinterpret_cast<const uint4 *>(k_head + b0 + lane_off);
-        sh.k1 = *reinterpret_cast<const uint4 *>(k_head + b1 + lane_off);
-        sh.v0 = *reinterpret_cast<const uint4 *>(v_head + b0 + lane_off);
-        sh.v1 = *reinterpret_cast<const uint4 *>(v_head + b1 + lane_off);
+        sh.k0 = *reinterpret_cast<const uint4 *>(k_head + b0);
+        sh.k1 = *reinterpret_cast<const uint4 *>(k_head + b1);
+        sh.v0 = *reinterpret_cast<const uint4 *>(v_head + b0);
+        sh.v1 = *reinterpret_cast<const uint4 *>(v_head + b1);
         return sh;
     };
     auto park = [&](int stage, const Share &sh) __attribute__((always_inline)) {
@@ -377,8 +399,11 @@ hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v
     const int ng = p.heads_per_chunk;
     const unsigned grid = unsigned(int64_t(p.num_q_heads / ng) * p.num_seqs * p.max_query_tiles);
     const dim3 g(grid), b(kThreads);
-    if (ng == 2) pa_prefill_mfma_kernel<2><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
-    else pa_prefill_mfma_kernel<1><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    const bool small = p.block_size < kTileTokens;
+    if (ng == 2 && !small) pa_prefill_mfma_kernel<2, false><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    else if (ng == 2) pa_prefill_mfma_kernel<2, true><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    else if (!small) pa_prefill_mfma_kernel<1, false><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    else pa_prefill_mfma_kernel<1, true><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
     return hipGetLastError();
 }
 

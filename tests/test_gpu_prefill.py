@@ -108,11 +108,26 @@ def test_long_recompute_sampled(oracle_mod):
         assert np.abs(got[pos] - ref[0]).max() <= BF16_TOL, pos
 
 
+@pytest.mark.parametrize("bs", [1, 2, 4, 8])
+def test_block_sizes_below_a_tile(oracle_mod, bs):
+    """A 16-token tile spans 2 to 16 blocks; table entries past the last needed block are -1."""
+    lens = [1, 15, 16, 33, 100, 257]
+    qlens = [1, 15, 7, 33, 100, 130]
+    w, q, qs = make(340 + bs, lens, qlens, 4, 2, bs=bs)
+    nblk = W.blocks_needed(w.context_lens, bs)
+    for n in range(len(lens)):
+        w.block_tables[n, nblk[n]:] = -1
+    check(oracle_mod, w, q, qs, f"block_size {bs}")
+
+
 def test_prefill_argument_errors():
     import paper_2503_13773_amd as K
-    w, q, qs = make(340, [20], [20], 4, 2, bs=8)
-    with pytest.raises(K.KvcError):                      # block_size 8 is not on this path
-        run(w, q, qs, 20)
+    w, q, qs = make(340, [20], [20], 4, 2)
+    kc = torch.from_numpy(W.bf16_bits_to_f32(w.k_cache)).cuda()          # fp32 is not on this path
+    with pytest.raises(K.KvcError):
+        K.paged_attention_prefill(torch.from_numpy(W.bf16_bits_to_f32(q)).cuda(), kc, kc.clone(),
+                                  torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(w.context_lens).cuda(),
+                                  torch.from_numpy(qs).cuda(), w.scale, 20)
 
 
 def test_context_beyond_32k_tokens_chunk(oracle_mod):
