@@ -169,8 +169,9 @@ KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int
  *   total_q, max_query_len   host-known: number of rows of q, and an upper bound on Qn (sizes
  *                 the launch grid; rows of sequences with Qn > max_query_len beyond it are not
  *                 computed).
- * Supported: bf16, head_dim 128, group <= 16, any block size the descriptor allows; everything
- * else returns KVC_ERR_UNSUPPORTED.  No workspace.  desc->max_context_len,
+ * Every shape the descriptor allows is served: bf16 with head_dim 128 and group <= 16 runs on
+ * the matrix cores (any block size), everything else (fp32, head_dim 64, larger groups) on the
+ * vector ALUs, one workgroup per query row and head chunk.  No workspace.  desc->max_context_len,
  * partition_tokens and kernel are ignored (must be valid).
  */
 KVC_API int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *v_cache,

@@ -362,12 +362,25 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     int rc = make_plan(desc, &pl);
     if (rc != KVC_OK) return rc;
     if (total_q < 0 || max_query_len < 0) return KVC_ERR_BAD_SHAPE;
-    if (desc->dtype != KVC_BF16 || desc->head_dim != 128 || desc->num_q_heads / desc->num_kv_heads > 16)
-        return KVC_ERR_UNSUPPORTED;
     if (desc->num_seqs == 0 || total_q == 0 || max_query_len == 0) return KVC_OK;
     if (!q_start) return KVC_ERR_NULL;
     rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
     if (rc != KVC_OK) return rc;
+    const bool on_mfma = desc->dtype == KVC_BF16 && desc->head_dim == 128 &&
+                         desc->num_q_heads / desc->num_kv_heads <= 16;
+    if (!on_mfma) {
+        // vector-ALU kernel, one query row per "sequence" of its grid, one partition, no workspace
+        kvc::AttnParams vp = make_params(*desc, pl, scale);
+        vp.num_seqs = total_q;
+        vp.partition_tokens = 1 << 30;
+        vp.max_partitions = 1;
+        const int64_t grid = int64_t(total_q) * (desc->num_q_heads / kvc::valu_head_chunk(vp.group));
+        if (grid > kMaxGrid) return KVC_ERR_BAD_SHAPE;
+        const hipError_t e = kvc::launch_prefill_valu(q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                      desc->num_seqs, max_query_len, out, vp, desc->dtype,
+                                                      desc->head_dim, int(grid), static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? KVC_OK : hip_failed(e);
+    }
     kvc::PrefillParams p;
     p.num_seqs = desc->num_seqs;
     p.num_q_heads = desc->num_q_heads;

@@ -77,6 +77,11 @@ hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v
                                const int32_t *block_tables, const int32_t *context_lens,
                                const int32_t *q_start, void *out, const PrefillParams &p,
                                hipStream_t stream);
+hipError_t launch_prefill_valu(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               const int32_t *q_start, int num_tables, int max_query_len, void *out,
+                               const AttnParams &p, int dtype, int head_dim, int grid,
+                               hipStream_t stream);
 hipError_t launch_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                                const int32_t *block_tables, const int32_t *positions, int num_seqs,
                                int num_kv_heads, int row_bytes, int block_size_log2,

@@ -12,6 +12,12 @@
 // the loop beyond the LR-lane dot-product reduction); the TPL groups, then the four
 // wavefronts, are merged with the log-sum-exp rule at the end.  Scores and softmax are
 // in natural-log units, accumulation in fp32.
+//
+// PREFILL variant (causal attention of several query positions per sequence, the recompute
+// path of Section 2.5 / 3.5, for the shapes the MFMA prefill kernel does not take): a
+// "sequence" of the grid is one query row; the row finds its sequence n by a search over
+// q_start, attends to the first S_n - Qn + i + 1 tokens of n's block list in one partition and
+// writes its normalised output directly.
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -57,10 +63,11 @@ struct Elem<uint16_t> {  // bfloat16 bit patterns
 
 constexpr int kUnroll = 4;  // tokens per lane group per loop trip (8 x 16-byte loads in flight)
 
-template <typename T, int D, int GC>
+template <typename T, int D, int GC, bool PREFILL>
 __global__ __launch_bounds__(kThreads) void pa_partial_valu_kernel(
     const T *__restrict__ q, const T *__restrict__ k_cache, const T *__restrict__ v_cache,
     const int32_t *__restrict__ block_tables, const int32_t *__restrict__ context_lens,
+    const int32_t *__restrict__ q_start, int num_tables, int max_query_len,
     T *__restrict__ out, Workspace ws, AttnParams p) {
     using E = Elem<T>;
     constexpr int EPL = E::kPerLane;
@@ -77,8 +84,22 @@ __global__ __launch_bounds__(kThreads) void pa_partial_valu_kernel(
     const int part = item / (chunks * p.num_seqs);
     const int head0 = hc * GC;
     const int kvh = head0 / p.group;
-    const int ctx = context_lens[seq];
     const int tid = threadIdx.x;
+    int ctx, tseq = seq;  // context length of this item, and the sequence whose table it walks
+    if (PREFILL) {
+        // seq is a row of q: largest n with q_start[n] <= row (sequences without rows are skipped)
+        int lo = 0, hi = num_tables;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (q_start[mid] <= seq) lo = mid; else hi = mid;
+        }
+        tseq = lo;
+        const int i = seq - q_start[lo], Qn = q_start[lo + 1] - q_start[lo], S = context_lens[lo];
+        if (Qn > S || i >= max_query_len) return;
+        ctx = S - Qn + i + 1;
+    } else {
+        ctx = context_lens[seq];
+    }
 
     if (ctx <= 0) {  // empty context: a row of zeros, written by partition 0
         if (part == 0)
@@ -107,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void pa_partial_valu_kernel(
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    const int32_t *table = block_tables + size_t(seq) * p.max_blocks_per_seq;
+    const int32_t *table = block_tables + size_t(tseq) * p.max_blocks_per_seq;
     const size_t head_stride = size_t(p.block_size) * D;               // elements per (block, kv head)
     const size_t block_stride = head_stride * p.num_kv_heads;
     constexpr int CH = TPL * kUnroll;                                   // tokens per wavefront per trip
@@ -226,14 +247,14 @@ __global__ __launch_bounds__(kThreads) void pa_partial_valu_kernel(
     }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool PREFILL>
 hipError_t launch_for_chunk(int gc, const void *q, const void *k, const void *v, const int32_t *bt,
-                            const int32_t *cl, void *out, Workspace ws, const AttnParams &p,
-                            int grid, hipStream_t stream) {
+                            const int32_t *cl, const int32_t *qs, int num_tables, int max_query_len,
+                            void *out, Workspace ws, const AttnParams &p, int grid, hipStream_t stream) {
 #define KVC_LAUNCH_VALU(GC)                                                                       \
-    pa_partial_valu_kernel<T, D, GC><<<dim3(grid), dim3(kThreads), 0, stream>>>(                  \
+    pa_partial_valu_kernel<T, D, GC, PREFILL><<<dim3(grid), dim3(kThreads), 0, stream>>>(         \
         static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v), bt, cl, \
-        static_cast<T *>(out), ws, p)
+        qs, num_tables, max_query_len, static_cast<T *>(out), ws, p)
     switch (gc) {
         case 8: KVC_LAUNCH_VALU(8); break;
         case 4: KVC_LAUNCH_VALU(4); break;
@@ -244,25 +265,46 @@ hipError_t launch_for_chunk(int gc, const void *q, const void *k, const void *v,
     return hipGetLastError();
 }
 
+template <bool PREFILL>
+hipError_t launch_for_type(const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, const int32_t *context_lens,
+                           const int32_t *q_start, int num_tables, int max_query_len, void *out,
+                           Workspace ws, const AttnParams &p, int dtype, int head_dim, int grid,
+                           hipStream_t stream) {
+    const int gc = valu_head_chunk(p.group);
+    if (dtype == KVC_F32) {
+        if (head_dim == 64)
+            return launch_for_chunk<float, 64, PREFILL>(gc, q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                        num_tables, max_query_len, out, ws, p, grid, stream);
+        return launch_for_chunk<float, 128, PREFILL>(gc, q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                     num_tables, max_query_len, out, ws, p, grid, stream);
+    }
+    if (head_dim == 64)
+        return launch_for_chunk<uint16_t, 64, PREFILL>(gc, q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                       num_tables, max_query_len, out, ws, p, grid, stream);
+    return launch_for_chunk<uint16_t, 128, PREFILL>(gc, q, k_cache, v_cache, block_tables, context_lens, q_start,
+                                                    num_tables, max_query_len, out, ws, p, grid, stream);
+}
+
 }  // namespace
 
 hipError_t launch_partial_valu(const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens, void *out,
                                Workspace ws, const AttnParams &p, int dtype, int head_dim,
                                int grid, hipStream_t stream) {
-    const int gc = valu_head_chunk(p.group);
-    if (dtype == KVC_F32) {
-        if (head_dim == 64)
-            return launch_for_chunk<float, 64>(gc, q, k_cache, v_cache, block_tables, context_lens,
-                                               out, ws, p, grid, stream);
-        return launch_for_chunk<float, 128>(gc, q, k_cache, v_cache, block_tables, context_lens,
-                                            out, ws, p, grid, stream);
-    }
-    if (head_dim == 64)
-        return launch_for_chunk<uint16_t, 64>(gc, q, k_cache, v_cache, block_tables, context_lens,
-                                              out, ws, p, grid, stream);
-    return launch_for_chunk<uint16_t, 128>(gc, q, k_cache, v_cache, block_tables, context_lens, out,
-                                           ws, p, grid, stream);
+    return launch_for_type<false>(q, k_cache, v_cache, block_tables, context_lens, nullptr, 0, 0, out, ws, p,
+                                  dtype, head_dim, grid, stream);
+}
+
+// p.num_seqs = rows of q, p.partition_tokens covers any context (one partition, no workspace).
+hipError_t launch_prefill_valu(const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               const int32_t *q_start, int num_tables, int max_query_len, void *out,
+                               const AttnParams &p, int dtype, int head_dim, int grid,
+                               hipStream_t stream) {
+    return launch_for_type<true>(q, k_cache, v_cache, block_tables, context_lens, q_start, num_tables,
+                                 max_query_len, out, Workspace{nullptr, nullptr, nullptr}, p, dtype, head_dim,
+                                 grid, stream);
 }
 
 }  // namespace kvc

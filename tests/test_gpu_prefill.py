@@ -5,26 +5,28 @@ import pytest
 import torch
 
 import kvc_workloads as W
-from gpu_util import BF16_TOL, dev_tensor, out_bits, out_to_f64
+from gpu_util import BF16_TOL, dev_tensor, out_bits, out_to_f64, tol_of
 
 pytestmark = pytest.mark.gpu
 
 
-def make(seed, lens, qlens, hq, hkv, bs=16):
+def make(seed, lens, qlens, hq, hkv, bs=16, dtype=W.BF16, d=128):
     rng = np.random.default_rng(seed)
     lens = np.asarray(lens, dtype=np.int32)
     nblk = W.blocks_needed(lens, bs)
-    w = W.build_workload("prefill", rng, dtype=W.BF16, context_lens=lens, num_q_heads=hq, num_kv_heads=hkv,
-                         head_dim=128, block_size=bs, max_blocks_per_seq=int(max(1, nblk.max())) + 1,
+    w = W.build_workload("prefill", rng, dtype=dtype, context_lens=lens, num_q_heads=hq, num_kv_heads=hkv,
+                         head_dim=d, block_size=bs, max_blocks_per_seq=int(max(1, nblk.max())) + 1,
                          num_pool_blocks=int(nblk.sum()) + 5)
     q_start = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
-    q = W.f32_to_bf16_bits(rng.standard_normal((int(q_start[-1]), hq, 128)).astype(np.float32))
+    q = rng.standard_normal((int(q_start[-1]), hq, d)).astype(np.float32)
+    if dtype == W.BF16:
+        q = W.f32_to_bf16_bits(q)
     return w, q, q_start
 
 
 def run(w, q, q_start, max_q):
     import paper_2503_13773_amd as K
-    out = K.paged_attention_prefill(dev_tensor(q, W.BF16), dev_tensor(w.k_cache, W.BF16), dev_tensor(w.v_cache, W.BF16),
+    out = K.paged_attention_prefill(dev_tensor(q, w.dtype), dev_tensor(w.k_cache, w.dtype), dev_tensor(w.v_cache, w.dtype),
                                     torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(w.context_lens).cuda(),
                                     torch.from_numpy(q_start).cuda(), w.scale, max_q)
     torch.cuda.synchronize()
@@ -36,12 +38,12 @@ def check(oracle_mod, w, q, q_start, label):
     max_q = int(np.diff(q_start).max())
     got = out_to_f64(run(w, q, q_start, max_q))
     ref = oracle_mod.paged_attention_prefill(q, w.k_cache, w.v_cache, w.block_tables, w.context_lens, q_start,
-                                             w.scale, dtype="bf16", num_threads=8)
+                                             w.scale, dtype=w.dtype, num_threads=8)
     rows = np.concatenate([np.arange(q_start[n], q_start[n + 1]) for n in range(len(w.context_lens))]) \
         if q_start[-1] else np.zeros(0, dtype=int)
     assert np.isfinite(got[rows]).all()
     err = np.abs(got[rows] - ref[rows]).max() if len(rows) else 0.0
-    assert err <= BF16_TOL, (label, err)
+    assert err <= tol_of(w), (label, err)
     return err
 
 
@@ -120,14 +122,30 @@ def test_block_sizes_below_a_tile(oracle_mod, bs):
     check(oracle_mod, w, q, qs, f"block_size {bs}")
 
 
+@pytest.mark.parametrize("dtype,d,hq,hkv,bs", [(W.F32, 64, 8, 2, 16), (W.F32, 128, 4, 4, 8), (W.BF16, 64, 8, 2, 16),
+                                                (W.BF16, 128, 32, 1, 16), (W.F32, 64, 6, 2, 1)])
+def test_shapes_off_the_matrix_core_path(oracle_mod, dtype, d, hq, hkv, bs):
+    """fp32, head_dim 64 and groups above 16 take the vector-ALU kernel (fp32: max-abs error <= 1e-5)."""
+    lens = [1, 17, 64, 150, 333]
+    qlens = [1, 17, 10, 0, 333]
+    w, q, qs = make(370 + d + hq, lens, qlens, hq, hkv, bs=bs, dtype=dtype, d=d)
+    check(oracle_mod, w, q, qs, f"valu {dtype} D={d} {hq}/{hkv} bs={bs}")
+
+
 def test_prefill_argument_errors():
     import paper_2503_13773_amd as K
     w, q, qs = make(340, [20], [20], 4, 2)
-    kc = torch.from_numpy(W.bf16_bits_to_f32(w.k_cache)).cuda()          # fp32 is not on this path
-    with pytest.raises(K.KvcError):
-        K.paged_attention_prefill(torch.from_numpy(W.bf16_bits_to_f32(q)).cuda(), kc, kc.clone(),
+    with pytest.raises(K.KvcError):                      # head_dim 32 is not a shape of this library
+        K.paged_attention_prefill(dev_tensor(q, W.BF16)[:, :, :32].contiguous(),
+                                  dev_tensor(w.k_cache, W.BF16)[..., :32].contiguous(),
+                                  dev_tensor(w.v_cache, W.BF16)[..., :32].contiguous(),
                                   torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(w.context_lens).cuda(),
                                   torch.from_numpy(qs).cuda(), w.scale, 20)
+    bad_qs = torch.from_numpy(qs).cuda()[:1]              # q_start must have num_seqs + 1 entries
+    with pytest.raises(TypeError):
+        K.paged_attention_prefill(dev_tensor(q, W.BF16), dev_tensor(w.k_cache, W.BF16), dev_tensor(w.v_cache, W.BF16),
+                                  torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(w.context_lens).cuda(),
+                                  bad_qs, w.scale, 20)
 
 
 def test_context_beyond_32k_tokens_chunk(oracle_mod):
