@@ -227,11 +227,26 @@ def main() -> int:
             if t_cpu >= 10.0 or t_cpu + t_cpu / passes > 30.0:
                 break
         cpu_s = t_cpu / passes
+        # the same step on one thread (a few passes, about 2 s)
+        t1, n1 = 0.0, 0
+        while t1 < 2.0 and n1 < 20:
+            t = time.perf_counter()
+            oracle.attention_of_workload(w, num_threads=1)
+            oracle.kv_block_copy(pool_np, h2, mapping_np)
+            t1 += time.perf_counter() - t
+            n1 += 1
+        model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+        except OSError:
+            pass
         cpu = {"value": round(step_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(threads),
                "kind": "oracle", "sample": f"{passes} full step(s) of the same batch ({w.num_seqs} seqs x "
                f"{w.num_q_heads} heads fp64 attention + {len(src_ids)}-block memcpy copy), "
-               f"{cpu_s:.2f} s per step", "s_per_step": round(cpu_s, 4)}
-        log(f"[bench] cpu oracle: {cpu_s:.2f} s/step on {threads} threads")
+               f"{cpu_s:.2f} s per step", "s_per_step": round(cpu_s, 4),
+               "single_thread_s_per_step": round(t1 / n1, 4), "cpu_model": model, "os_cpu_count": os.cpu_count()}
+        log(f"[bench] cpu oracle: {cpu_s:.3f} s/step on {threads} threads, {t1 / n1:.3f} s/step on 1 thread ({model})")
 
     # ---- measured HBM traffic of the dominant kernel, if a rocprofv3 --pmc summary is committed ----
     traffic = None
