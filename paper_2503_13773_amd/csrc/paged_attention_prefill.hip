@@ -13,20 +13,27 @@
 // per load instruction), parked in LDS, and read from there by all four wavefronts as MFMA
 // operands: measured with one private copy per wavefront, the vector memory pipeline (about 40
 // cache look-ups per 16-byte-per-lane load instruction) was busy 92 % of the time and bound the
-// kernel.  LDS holds two steps, so the loads of step s+2 are in flight and step s+1 is being
-// written while step s is consumed; one barrier per step.
+// kernel.  LDS holds three steps of K and four of V, so that global loads, LDS writes, LDS reads
+// and the arithmetic of four consecutive steps overlap; one barrier per step.
 //
 // Per step and head: S = K . Q^T for the two 16-token tiles (8 x v_mfma_f32_16x16x32_bf16),
 // one online-softmax update over the 32 tokens, and O^T += V^T . P^T with the 32 tokens as the
 // depth of 8 more 32-deep MFMAs: the C layout of the two score tiles (lane holds tokens
 // 4*quad + i of each) is taken as the B operand as it stands, which fixes the order in which
 // the 32 tokens fill the depth slots (slot 8*quad + i = token 4*quad + i of the first tile,
-// slot 8*quad + 4 + i the same of the second); the register transpose of V (shared by the NG
-// heads) builds its A operand in the same order.  The running sum of the weights is one more
-// MFMA against an all-ones A operand, so it adds up exactly the bf16-rounded weights that
-// multiply V and needs no cross-lane reduction.  K rows are stored in LDS with their 16-byte
-// chunks XOR-permuted by the row number, which makes the A-operand reads (16 lanes = 16 rows,
-// same columns) conflict free; V is read row-wise and needs no permutation.
+// slot 8*quad + 4 + i the same of the second); the A operand V^T (shared by the NG heads) comes
+// from LDS in that order by transposing reads (ds_read_b64_tr_b16; V rows are padded to 288
+// bytes so that the 8 rows a half-wavefront touches fall into different banks).  The running
+// sum of the weights is one more MFMA against an all-ones A operand, so it adds up exactly the
+// bf16-rounded weights that multiply V and needs no cross-lane reduction.  K rows are stored in
+// LDS with their 16-byte chunks XOR-permuted by the row number, which makes the A-operand reads
+// (16 lanes = 16 rows, same columns) conflict free.
+//
+// The steps are software-pipelined: a turn of the loop issues the score MFMAs of step s+1 (the
+// K operands of its first tile were read from LDS during the previous turn, so they start
+// without an LDS wait) together with the exponentials, the P.V MFMAs of step s and the max tree
+// of step s+1, so matrix-core and vector work of neighbouring steps overlap inside a wavefront
+// as well as between the two wavefronts of a SIMD.
 //
 // The causal mask only bites in the last one or two steps of a wavefront: steps entirely
 // below the diagonal of all 16 rows run code without mask or range checks.  Token 0 is visible
@@ -54,7 +61,9 @@ constexpr int kStepTiles = 2;
 constexpr int kStepTokens = kStepTiles * kTileTokens;
 constexpr int kStepElems = kStepTiles * kTileElems;
 constexpr float kLazyLog2 = 8.0f;
-constexpr int kStages = 3;
+constexpr int kKStages = 3;   // K rows of steps s+1 .. s+3 during turn s
+constexpr int kVStages = 4;   // V rows of steps s .. s+3
+constexpr int kPreTiles = 1;   // tiles of the next step whose K operands are read one turn ahead (2 measured the same)
 constexpr int kVRow = D + 16;                     // padded V row in LDS (288 bytes): see the transpose reads
 constexpr int kVStepElems = kStepTokens * kVRow;
 
@@ -88,25 +97,24 @@ __device__ inline float max_over_quads(float x) {
     return b0 > b1 ? b0 : b1;
 }
 
-// Scores of one 32-token step: S = K . Q^T for the two 16-token tiles of every head, K rows
-// read from LDS (sk: [32 tokens][128], 16-byte chunks XOR-permuted by the row number).
+// K operands of one 16-token tile from LDS (sk_tile: [16 tokens][128], 16-byte chunks
+// XOR-permuted by the row number).
+__device__ inline void read_k_tile(bf16x8 (&ka)[4], const uint16_t *sk_tile, int quad, int r) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        ka[j] = *reinterpret_cast<const bf16x8 *>(sk_tile + r * D + (((4 * j + quad) ^ r) << 3));
+}
+
+// Scores of one tile for every head: S = K . Q^T.
 template <int NG>
-__device__ inline void step_scores(floatx4 (&s)[NG][kStepTiles], const uint16_t *sk,
-                                   const bf16x8 (&qb)[NG][4], int quad, int r) {
-    bf16x8 ka[kStepTiles][4];
+__device__ inline void tile_scores(floatx4 (&s)[NG][kStepTiles], int t, const bf16x8 (&ka)[4],
+                                   const bf16x8 (&qb)[NG][4]) {
 #pragma unroll
-    for (int t = 0; t < kStepTiles; ++t)
+    for (int g = 0; g < NG; ++g) {
+        s[g][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            ka[t][j] = *reinterpret_cast<const bf16x8 *>(sk + t * kTileElems + r * D + (((4 * j + quad) ^ r) << 3));
-#pragma unroll
-    for (int g = 0; g < NG; ++g)
-#pragma unroll
-        for (int t = 0; t < kStepTiles; ++t) {
-            s[g][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) s[g][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][j], qb[g][j], s[g][t], 0, 0, 0);
-        }
+        for (int j = 0; j < 4; ++j) s[g][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j], qb[g][j], s[g][t], 0, 0, 0);
+    }
 }
 
 // Scaled (and, if MASKED, causally masked) scores of one head and their max over the step's
@@ -145,15 +153,16 @@ __device__ inline void rebase(PrefillState &st, float mx) {
 // One turn of the software pipeline: the weights and the P.V accumulation of step `cur` (scaled
 // scores in x, V rows in sv_cur) together with the scores, scaling and max of step `next` (K rows
 // in sk_next), in one straight-line region so that the matrix-core work of one step runs under
-// the vector work of the other.  On return x holds the scaled scores of step `next` and the
-// reference points are rebased for it.
+// the vector work of the other.  On return x holds the scaled scores of step `next`, the
+// reference points are rebased for it, and ka_pre holds K operands of the step after `next`.
 // MASKED: `vlim_cur` = tokens of step cur visible to any column of this wavefront (V rows past
 // it are zeroed: their weights are zero for every column and the rows may hold NaN);
 // `limit_next` = tokens of step next visible to this lane's column.
 template <int NG, bool MASKED>
-__device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], const uint16_t *sk_next,
-                                     const uint16_t *sv_cur, const bf16x8 (&qb)[NG][4], float scale_log2e,
-                                     int vlim_cur, int limit_next, int quad, int r) {
+__device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], bf16x8 (&ka_pre)[kStepTiles][4],
+                                     const uint16_t *sk_next, const uint16_t *sk_next2, const uint16_t *sv_cur,
+                                     const bf16x8 (&qb)[NG][4], float scale_log2e, int vlim_cur, int limit_next,
+                                     int quad, int r) {
     // A operands of O^T += V^T . P^T straight from LDS: the transpose read hands lane i of a
     // 16-lane block the i-th 16-bit element of each of the four 16-element groups that lanes
     // 4k .. 4k+3 of the block point at (8 bytes each).  Lanes 4k .. 4k+3 of block `quad` point at
@@ -183,8 +192,22 @@ __device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], 
         }
     }
 
+    // scores of step next: the first kPreTiles tiles from operands read during the previous turn
+    // (no LDS wait in front of the first MFMAs), the rest from LDS now; then the operands of the
+    // step after next are read for the coming turn
     floatx4 s[NG][kStepTiles];
-    step_scores<NG>(s, sk_next, qb, quad, r);
+#pragma unroll
+    for (int t = 0; t < kStepTiles; ++t) {
+        if (t < kPreTiles) {
+            tile_scores<NG>(s, t, ka_pre[t], qb);
+        } else {
+            bf16x8 ka[4];
+            read_k_tile(ka, sk_next + t * kTileElems, quad, r);
+            tile_scores<NG>(s, t, ka, qb);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kPreTiles; ++t) read_k_tile(ka_pre[t], sk_next2 + t * kTileElems, quad, r);
 
     // weights of step cur, rounded to bf16: the B operand of P.V as they stand
     bf16x8 pb[NG];
@@ -225,8 +248,8 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma_kernel(
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
     uint16_t *__restrict__ out, PrefillParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t s_k[kStages][kStepElems];
-    __shared__ __attribute__((aligned(16))) uint16_t s_v[kStages][kVStepElems];
+    __shared__ __attribute__((aligned(16))) uint16_t s_k[kKStages][kStepElems];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[kVStages][kVStepElems];
 
     // blockIdx.x = head chunk + chunks * (seq + num_seqs * reversed query tile)
     const int chunks = p.num_q_heads / NG;
@@ -322,50 +345,66 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma_kernel(
         sh.v1 = *reinterpret_cast<const uint4 *>(v_head + b1);
         return sh;
     };
-    auto park = [&](int stage, const Share &sh) __attribute__((always_inline)) {
-        *reinterpret_cast<uint4 *>(&s_k[stage][k_dst]) = sh.k0;
-        *reinterpret_cast<uint4 *>(&s_k[stage][kTileElems + k_dst]) = sh.k1;
-        *reinterpret_cast<uint4 *>(&s_v[stage][v_dst]) = sh.v0;
-        *reinterpret_cast<uint4 *>(&s_v[stage][kTileTokens * kVRow + v_dst]) = sh.v1;
+    auto park = [&](int kstage, int vstage, const Share &sh) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(&s_k[kstage][k_dst]) = sh.k0;
+        *reinterpret_cast<uint4 *>(&s_k[kstage][kTileElems + k_dst]) = sh.k1;
+        *reinterpret_cast<uint4 *>(&s_v[vstage][v_dst]) = sh.v0;
+        *reinterpret_cast<uint4 *>(&s_v[vstage][kTileTokens * kVRow + v_dst]) = sh.v1;
     };
 
-    // Step s lives in stage s % 3.  Turn s first parks step s+2 (fetched during turn s-1) over
-    // step s-1, whose last reader passed the barrier that ended turn s-1, and issues the fetch of
-    // step s+3; then it reads the K rows of step s+1 and the V rows of step s.  The barrier at its
-    // end publishes step s+2 for turn s+1.  Past the last step the last one is fetched and parked
-    // again (unused) to keep the loop branch free.
-    Share next = fetch(ids_of(0));
-    park(0, next);
-    next = fetch(ids_of(min(1, wg_steps - 1)));
-    park(1, next);
-    next = fetch(ids_of(min(2, wg_steps - 1)));
-    Ids ids = ids_of(min(3, wg_steps - 1));
+    // K rows of step j live in K stage j % 3, V rows in V stage j % 4.  Turn s parks step s+3
+    // (fetched during turn s-1) over K(s) and V(s-1), whose last readers passed the barrier that
+    // ended turn s-1, and issues the fetch of step s+4; it computes the scores of step s+1
+    // (operands read during turn s-1, or from K stage (s+1) % 3), reads operands of step s+2 for
+    // the next turn and the V rows of step s.  The barrier at its end publishes step s+3.  Past
+    // the last step the last one is fetched and parked again (unused): the loop stays branch free.
+    {
+        const Share d0 = fetch(ids_of(0));
+        const Share d1 = fetch(ids_of(min(1, wg_steps - 1)));
+        park(0, 0, d0);
+        park(1, 1, d1);
+    }
+    Share next = fetch(ids_of(min(2, wg_steps - 1)));
     __syncthreads();
 
     float x[NG][8];
-    if (active) {  // scores of step 0
+    bf16x8 ka_pre[kStepTiles][4];
+    if (active) {  // scores of step 0, then the operands turn 0 starts from
         floatx4 s[NG][kStepTiles];
-        step_scores<NG>(s, s_k[0], qb, quad, r);
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t) {
+            bf16x8 ka[4];
+            read_k_tile(ka, s_k[0] + t * kTileElems, quad, r);
+            tile_scores<NG>(s, t, ka, qb);
+        }
 #pragma unroll
         for (int g = 0; g < NG; ++g) rebase(st[g], scale_mask_max<true>(x[g], s[g], p.scale_log2e, my_pos + 1, quad));
+#pragma unroll
+        for (int t = 0; t < kPreTiles; ++t) read_k_tile(ka_pre[t], s_k[1] + t * kTileElems, quad, r);
     }
-    int cur = 0, nxt = 1, wr = 2;
+    park(2, 2, next);  // K stage 2 and V stage 2 have not been used yet
+    next = fetch(ids_of(min(3, wg_steps - 1)));
+    Ids ids = ids_of(min(4, wg_steps - 1));
+    __syncthreads();
+
+    int k0 = 0, k1 = 1, k2 = 2;  // K stages of steps s, s+1, s+2
     for (int s = 0; s < wg_steps; ++s) {
-        park(wr, next);
+        park(k0, (s + 3) & 3, next);
         next = fetch(ids);
-        ids = ids_of(min(s + 4, wg_steps - 1));
+        ids = ids_of(min(s + 5, wg_steps - 1));
         if (active) {
             if (s + 1 < free_steps)
-                pipeline_turn<NG, false>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, kStepTokens, kStepTokens, quad, r);
+                pipeline_turn<NG, false>(st, x, ka_pre, s_k[k1], s_k[k2], s_v[s & 3], qb, p.scale_log2e, kStepTokens,
+                                         kStepTokens, quad, r);
             else
-                pipeline_turn<NG, true>(st, x, s_k[nxt], s_v[cur], qb, p.scale_log2e, wave_vis - s * kStepTokens,
-                                        my_pos + 1 - (s + 1) * kStepTokens, quad, r);
+                pipeline_turn<NG, true>(st, x, ka_pre, s_k[k1], s_k[k2], s_v[s & 3], qb, p.scale_log2e,
+                                        wave_vis - s * kStepTokens, my_pos + 1 - (s + 1) * kStepTokens, quad, r);
         }
         __syncthreads();
-        const int t = cur;
-        cur = nxt;
-        nxt = wr;
-        wr = t;
+        const int t = k0;
+        k0 = k1;
+        k1 = k2;
+        k2 = t;
     }
 
     if (!active) return;
