@@ -52,6 +52,7 @@ def main() -> int:
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA fixed partitions, 3 same with LDS-staged K, 4 MFMA balanced")
     ap.add_argument("--partition-tokens", type=int, default=0)
     ap.add_argument("--block-size", type=int, default=16, help="tokens per KV block (the configs use 16)")
+    ap.add_argument("--num-seqs", type=int, default=0, help="override the batch size of the workload (0 = as named)")
     ap.add_argument("--replica-bytes", type=float, default=2.2e9,
                     help="rotate over replicas of the batch totalling at least this many KV bytes")
     ap.add_argument("--swap-frac", type=float, default=0.20)
@@ -77,7 +78,7 @@ def main() -> int:
     lib = K.lib()
 
     t0 = time.time()
-    w = W.make_config(args.workload, block_size=args.block_size)
+    w = W.make_config(args.workload, block_size=args.block_size, **({"num_seqs": args.num_seqs} if args.num_seqs else {}))
     log(f"[bench] workload {args.workload}: {w.num_seqs} seqs, mean ctx {w.context_lens.mean():.0f}, "
         f"max {w.max_context_len}, pool {w.num_pool_blocks} blocks, KV {w.kv_bytes()/1e6:.1f} MB "
         f"(generated in {time.time()-t0:.1f}s)")
