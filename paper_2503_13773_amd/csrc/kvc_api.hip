@@ -47,7 +47,7 @@ bool mfma_ok(const kvc_attn_desc &d) {
 bool balanced_ok(const kvc_attn_desc &d, int max_ctx) {
     return d.dtype == KVC_BF16 && d.head_dim == 128 && d.block_size >= 4 &&
            d.num_q_heads / d.num_kv_heads <= 16 && d.num_seqs <= kvc::kMaxStreamSeqs &&
-           int64_t(d.num_seqs) * d.num_kv_heads * ceil_div(max_ctx, 16) < (int64_t(1) << 30) &&
+           int64_t(d.num_seqs) * d.num_kv_heads * (ceil_div(max_ctx, 16) + 1) < (int64_t(1) << 30) &&
            int64_t(d.num_pool_blocks) * d.num_kv_heads * std::max(1, d.block_size / 16) < (int64_t(1) << 31);
 }
 

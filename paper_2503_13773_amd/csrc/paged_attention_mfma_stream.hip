@@ -7,9 +7,14 @@
 // a ragged tail.  Here instead the work is flattened and cut into equal pieces:
 //
 //   rows  = (sequence n, KV head g), each with t_n = ceil(context_len_n / 16) tiles
-//   flat  = [row 0 tiles][row 1 tiles]...   T = num_kv_heads * sum_n t_n tiles in all
+//   flat  = [row 0 tiles][row 0 cost][row 1 tiles][row 1 cost]...
+//           T = num_kv_heads * sum_n (t_n + kRowCost) units in all
 //   every WAVEFRONT of the grid is a worker that takes C = max(C_min, ceil(T / workers))
-//   consecutive flat tiles.
+//   consecutive flat units.
+// The kRowCost units after a row's tiles stand for the work of leaving the row (writing the
+// segment, switching the softmax state, loading the next Q: measured at about half a tile's
+// time each; a worker that crossed 9 short rows finished 6 us after the rest); nothing is
+// computed for them, they only make a worker that crosses rows take fewer tiles.
 //
 // The grid is ONE wavefront per SIMD (256 CUs x 4).  Measured on MI355X: with 2 or 3
 // wavefronts per SIMD the older wavefronts win the memory-issue arbitration, the younger
@@ -49,13 +54,14 @@ __device__ inline int uniform(int x) { return __builtin_amdgcn_readfirstlane(x);
 
 constexpr int kStageTiles = 256;  // tiles whose addresses are staged in LDS per wavefront at a time
 constexpr int kMaxUnits = 4;      // a 16-token tile spans up to 4 blocks (block_size 4)
+constexpr int kRowCost = 1;       // flat units charged for leaving a row
 
 // A row of the flattened work: (sequence, KV head); all fields wavefront-uniform.
 struct RowCursor {
     int n;       // sequence
     int kvh;     // KV head
-    int pref;    // tiles of all sequences before n
-    int tiles;   // t_n
+    int pref;    // flat units (per KV head) of all sequences before n
+    int tiles;   // t_n (the row spans t_n + kRowCost flat units)
 };
 
 __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
@@ -63,7 +69,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
     AttnParams p, int unit_log2, int units_per_block_log2) {
-    __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of tiles per sequence (+ guard)
+    __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of flat units (tiles + row cost) per sequence (+ guard)
     __shared__ int s_ctx[kMaxStreamSeqs];       // context length per sequence
     __shared__ int s_wave_tot[kWaves];
     __shared__ int s_tile[kWaves][kStageTiles * kMaxUnits];  // per worker: pool index of each unit of its next tiles
@@ -85,6 +91,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
                 const int c = max(context_lens[n], 0);
                 s_ctx[n] = c;
                 t = (c + kTileTokens - 1) >> 4;
+                if (t > 0) t += kRowCost;
             }
             local[i] = sum;
             sum += t;
@@ -107,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         }
         if (tid == kThreads - 1) {
             s_pref[nseq] = excl + sum;
-            s_pref[nseq + 1] = excl + sum + 1;  // guard: "sequence nseq" looks non-empty, stops row walks
+            s_pref[nseq + 1] = excl + sum + 1 + kRowCost;  // guard: "sequence nseq" looks non-empty, stops row walks
         }
         __syncthreads();
     }
@@ -120,7 +127,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const int worker = blockIdx.x * kWaves + wave;
     if (int64_t(worker) * C >= T) return;
     const int f0 = worker * C;
-    const int NT = min(T, f0 + C) - f0;  // tiles of this worker, >= 1
+    const int f1 = min(T, f0 + C);       // the worker's flat units are [f0, f1)
 
 
     // Row after `c` in flat order, skipping empty sequences.  Past the last row it parks on
@@ -132,7 +139,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             o.kvh = 0;
             do { ++o.n; } while (uniform(s_pref[o.n + 1]) == uniform(s_pref[o.n]));
             o.pref = uniform(s_pref[o.n]);
-            o.tiles = uniform(s_pref[o.n + 1]) - o.pref;
+            o.tiles = uniform(s_pref[o.n + 1]) - o.pref - kRowCost;
         }
         return o;
     };
@@ -144,6 +151,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
 
     // ---- place the worker: largest n with s_pref[n] * Hkv <= f0 (that sequence is not empty)
     RowCursor first;
+    int first_tile;
     {
         int lo = 0, hi = nseq;
         while (hi - lo > 1) {
@@ -152,10 +160,30 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         }
         first.n = lo;
         first.pref = uniform(s_pref[lo]);
-        first.tiles = uniform(s_pref[lo + 1]) - first.pref;
-        first.kvh = (f0 - first.pref * Hkv) / first.tiles;
+        const int units = uniform(s_pref[lo + 1]) - first.pref;  // per KV head
+        first.tiles = units - kRowCost;
+        first.kvh = (f0 - first.pref * Hkv) / units;
+        first_tile = (f0 - first.pref * Hkv) - first.kvh * units;
+        if (first_tile >= first.tiles) {  // the range starts in the row's cost units: begin with the next row
+            first = next_row(first);
+            first_tile = 0;
+        }
     }
-    const int first_tile = (f0 - first.pref * Hkv) - first.kvh * first.tiles;
+    // tiles of this worker: the part of [f0, f1) that falls on tiles rather than cost units
+    int NT = 0;
+    {
+        RowCursor c = first;
+        int t0 = first_tile;
+        while (c.n < nseq) {
+            const int row0 = c.pref * Hkv + c.kvh * (c.tiles + kRowCost);  // flat unit of the row's tile 0
+            if (row0 + t0 >= f1) break;
+            NT += min(row0 + c.tiles, f1) - (row0 + t0);
+            if (row0 + c.tiles + kRowCost >= f1) break;
+            c = next_row(c);
+            t0 = 0;
+        }
+    }
+    if (NT == 0) return;  // the range covered cost units only; no row counts this worker
 
     // ---- tile addresses of the worker's range, staged in LDS
     // A "unit" is the part of a 16-token tile that lies in one block: min(block_size, 16)
@@ -231,7 +259,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     // Write the finished segment [seg_first, tc) of row rc.
     auto finalize = [&]() __attribute__((always_inline)) {
         st.finish();
-        const int row_f = rc.pref * Hkv + rc.kvh * rc.tiles;  // flat index of the row's tile 0
+        const int row_f = rc.pref * Hkv + rc.kvh * (rc.tiles + kRowCost);  // flat unit of the row's tile 0
         const int j0 = row_f / C;
         const int cnt = (row_f + rc.tiles - 1) / C - j0 + 1;  // workers that touch this row
         const int slot = worker - j0;                         // my partial index within the row
