@@ -70,7 +70,7 @@ typedef enum {
     KVC_KERNEL_MFMA_LDS = 3, /* same, K tiles loaded fully coalesced and re-laid-out through LDS */
     KVC_KERNEL_MFMA_BALANCED = 4 /* matrix-core tiles, persistent grid: the batch's (sequence, kv head,
                             16-token tile) work is flattened and cut into equal per-wavefront ranges;
-                            bf16, head_dim 128, block_size >= 4, group <= 16, num_seqs <= 1024 */
+                            bf16, head_dim 128, block_size >= 4, group <= 16, num_seqs <= 4096 */
 } kvc_kernel;
 
 typedef struct {

@@ -53,7 +53,7 @@ struct Workspace {
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup, every attention kernel
 constexpr int kWaves = kThreads / 64;
 constexpr int kNumCUs = 256;        // MI355X
-constexpr int kMaxStreamSeqs = 1024;  // batch limit of the balanced kernel (prefix sum lives in LDS)
+constexpr int kMaxStreamSeqs = 4096;  // batch limit of the balanced kernel (prefix sum lives in LDS)
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the
 // hipError_t of the launch.

@@ -1,5 +1,5 @@
 // Load-balanced persistent partial kernel of paged decode attention on the matrix cores
-// (gfx950, bf16, head_dim 128, block_size >= 4, group <= 16, <= 1024 sequences).
+// (gfx950, bf16, head_dim 128, block_size >= 4, group <= 16, <= 4096 sequences).
 //
 // The serving traces this path sees have heavily skewed context lengths (a lognormal mix:
 // median ~700 tokens, tail to 4096), and the whole batch is only ~30 us of HBM streaming.
@@ -37,7 +37,7 @@
 // the row after the current one are prefetched when a cursor enters a row, so a row change
 // costs no dependent-load bubble.
 //
-// Start-up (once per workgroup): prefix sum of t_n over the batch in LDS (<= 1024 sequences),
+// Start-up (once per workgroup): prefix sum of t_n over the batch in LDS (<= 4096 sequences),
 // then a binary search places each worker.  Per tile the arithmetic is pa_mfma_tile.h.
 #include <math.h>
 
@@ -64,13 +64,17 @@ struct RowCursor {
     int tiles;   // t_n (the row spans t_n + kRowCost flat units)
 };
 
+// MAXSPT: sequences per thread in the start-up prefix sum (batches up to MAXSPT * 256 sequences);
+// the small instance keeps the start-up of ordinary batches short.
+template <int MAXSPT>
 __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
     AttnParams p, int unit_log2, int units_per_block_log2) {
-    __shared__ int s_pref[kMaxStreamSeqs + 2];  // exclusive prefix of flat units (tiles + row cost) per sequence (+ guard)
-    __shared__ int s_ctx[kMaxStreamSeqs];       // context length per sequence
+    constexpr int kSeqs = MAXSPT * kThreads;
+    __shared__ int s_pref[kSeqs + 2];  // exclusive prefix of flat units (tiles + row cost) per sequence (+ guard)
+    __shared__ int s_ctx[kSeqs];       // context length per sequence
     __shared__ int s_wave_tot[kWaves];
     __shared__ int s_tile[kWaves][kStageTiles * kMaxUnits];  // per worker: pool index of each unit of its next tiles
 
@@ -81,10 +85,11 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
 
     // ---- prefix sum of 16-token tiles per sequence (thread t owns sequences t*spt .. +spt-1)
     {
-        const int spt = (nseq + kThreads - 1) / kThreads;  // <= 4
-        int local[4], sum = 0;
+        constexpr int kMaxSpt = MAXSPT;
+        const int spt = (nseq + kThreads - 1) / kThreads;  // <= kMaxSpt
+        int local[kMaxSpt], sum = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kMaxSpt; ++i) {
             const int n = tid * spt + i;
             int t = 0;
             if (i < spt && n < nseq) {
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         for (int w = 0; w < wave; ++w) base += s_wave_tot[w];
         const int excl = base + inc - sum;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kMaxSpt; ++i) {
             const int n = tid * spt + i;
             if (i < spt && n < nseq) s_pref[n] = excl + local[i];
         }
@@ -348,10 +353,16 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
     } else {
         while ((16 << upb_log2) < p.block_size) ++upb_log2;
     }
-    pa_stream_mfma_kernel<<<dim3(grid), dim3(kThreads), 0, stream>>>(
-        static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
-        static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
-        static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
+    if (p.num_seqs <= 4 * kThreads)
+        pa_stream_mfma_kernel<4><<<dim3(grid), dim3(kThreads), 0, stream>>>(
+            static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+            static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
+            static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
+    else
+        pa_stream_mfma_kernel<kMaxStreamSeqs / kThreads><<<dim3(grid), dim3(kThreads), 0, stream>>>(
+            static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+            static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
+            static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
     return hipGetLastError();
 }
 

@@ -318,15 +318,15 @@ def test_runs_on_a_side_stream_and_validates_inputs():
     assert K.validate_attention_inputs(d["tables"], long, desc) == -8
 
 
-@pytest.mark.parametrize("nseq", [1024, 1100])
+@pytest.mark.parametrize("nseq", [1100, 4096, 4200])
 def test_large_batches_of_short_sequences(oracle_mod, nseq):
-    """1024 sequences is the limit of the balanced kernel (its prefix sum lives in LDS), 1100 takes
-    the fixed-partition kernel; contexts of 1 to 80 tokens make every worker cross many rows."""
+    """4096 sequences is the limit of the balanced kernel (its prefix sum lives in LDS), 4200 takes
+    the fixed-partition kernel; contexts of 0 to 80 tokens make every worker cross many rows."""
     import paper_2503_13773_amd as K
     rng = np.random.default_rng(500 + nseq)
     lens = rng.integers(0, 81, nseq).astype(np.int32)
     w = custom(500 + nseq, dtype=W.BF16, lens=lens, hq=8, hkv=2, d=128, bs=16, name=f"short{nseq}")
     d = to_device(w)
     plan = K.attn_plan(K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=80))
-    assert plan.kernel == (BALANCED if nseq <= 1024 else MFMA)
+    assert plan.kernel == (BALANCED if nseq <= 4096 else MFMA)
     check(w, oracle_mod, f"{nseq} short sequences")
