@@ -97,7 +97,7 @@ def test_plan_picks_kernels_and_sizes_workspace(K):
     assert rc == 0 and p.kernel == K.KERNEL_MFMA_BALANCED
     rc, p = plan_status(K, desc(K, block_size=2))
     assert rc == 0 and p.kernel == K.KERNEL_VALU
-    rc, p = plan_status(K, desc(K, num_seqs=2000))          # too many sequences for the balanced kernel
+    rc, p = plan_status(K, desc(K, num_seqs=5000))          # too many sequences for the balanced kernel
     assert rc == 0 and p.kernel == K.KERNEL_MFMA
     rc, p = plan_status(K, desc(K, kernel=K.KERNEL_MFMA, partition_tokens=512))
     assert rc == 0 and p.partition_tokens == 512 and p.max_partitions == 8 and p.partial_grid == 64 * 8 * 8
