@@ -113,7 +113,7 @@ def test_plan_picks_kernels_and_sizes_workspace(K):
     (dict(partition_tokens=(1 << 20) + 16, kernel=4), -2), (dict(kernel=9), -2),
     (dict(reserved=1), -2), (dict(num_seqs=-1), -2), (dict(max_blocks_per_seq=0), -2),
     (dict(kernel=2, dtype=0), -4), (dict(kernel=2, num_q_heads=32, num_kv_heads=1), -4),
-    (dict(kernel=4, num_seqs=1025), -4), (dict(kernel=3, block_size=8), -4),
+    (dict(kernel=4, num_seqs=4097), -4), (dict(kernel=3, block_size=8), -4),
 ])
 def test_bad_descriptors_are_rejected(K, kw, status):
     rc, _ = plan_status(K, desc(K, **kw))
