@@ -150,6 +150,66 @@ __device__ inline void rebase(PrefillState &st, float mx) {
     }
 }
 
+// A operands of O^T += V^T . P^T straight from LDS: the transpose read hands lane i of a 16-lane
+// block the i-th 16-bit element of each of the four 16-element groups that lanes 4k .. 4k+3 of
+// the block point at (8 bytes each).  Lanes 4k .. 4k+3 of block `quad` point at dims 16e + 0, 4,
+// 8, 12 of token 4*quad + k, so lane r receives dim 16e + r of tokens 4*quad .. +3: the depth
+// slots in the order the score layout fixed.  MASKED: rows at or past `vlim` (tokens of the step
+// visible to any column of this wavefront) are zeroed: their weights are zero for every column
+// and the rows may hold NaN.
+template <bool MASKED>
+__device__ inline void read_v_operands(uint2 (&va)[8][kStepTiles], const uint16_t *sv, int vlim, int quad, int r) {
+    typedef short v4i16 __attribute__((ext_vector_type(4)));
+    typedef v4i16 __attribute__((address_space(3))) * lds_v4i16_ptr;
+    const uint16_t *vlane = sv + (4 * quad + (r >> 2)) * kVRow + 4 * (r & 3);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t)
+            va[e][t] = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                     (lds_v4i16_ptr)(vlane + t * kTileTokens * kVRow + 16 * e)));
+    if (MASKED) {
+#pragma unroll
+        for (int t = 0; t < kStepTiles; ++t) {
+            const int tok = t * kTileTokens + 4 * quad;
+            const uint32_t m01 = (tok < vlim ? 0xffffu : 0u) | (tok + 1 < vlim ? 0xffff0000u : 0u);
+            const uint32_t m23 = (tok + 2 < vlim ? 0xffffu : 0u) | (tok + 3 < vlim ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                va[e][t].x &= m01;
+                va[e][t].y &= m23;
+            }
+        }
+    }
+}
+
+// O^T += V^T . P^T for every head, and the running weight sums as one more MFMA against an
+// all-ones A operand.
+template <int NG>
+__device__ inline void accumulate_pv(PrefillState (&st)[NG], const uint2 (&va)[8][kStepTiles], const bf16x8 (&pb)[NG]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint4 aw = {va[e][0].x, va[e][0].y, va[e][1].x, va[e][1].y};
+        const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+            st[g].acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[g], st[g].acc[e], 0, 0, 0);
+    }
+    const uint4 one_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, one_bits);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) st[g].lsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[g], st[g].lsum, 0, 0, 0);
+}
+
+// Weights of a step from its scaled scores, rounded to bf16: the B operand of P.V as they stand.
+__device__ inline bf16x8 step_weights(const float (&x)[8], float m) {
+    float pf[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(x[i] - m);
+    const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]), pack_bf16(pf[6], pf[7])};
+    return __builtin_bit_cast(bf16x8, pw);
+}
+
 // One turn of the software pipeline: the weights and the P.V accumulation of step `cur` (scaled
 // scores in x, V rows in sv_cur) together with the scores, scaling and max of step `next` (K rows
 // in sk_next), in one straight-line region so that the matrix-core work of one step runs under
@@ -163,34 +223,8 @@ __device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], 
                                      const uint16_t *sk_next, const uint16_t *sk_next2, const uint16_t *sv_cur,
                                      const bf16x8 (&qb)[NG][4], float scale_log2e, int vlim_cur, int limit_next,
                                      int quad, int r) {
-    // A operands of O^T += V^T . P^T straight from LDS: the transpose read hands lane i of a
-    // 16-lane block the i-th 16-bit element of each of the four 16-element groups that lanes
-    // 4k .. 4k+3 of the block point at (8 bytes each).  Lanes 4k .. 4k+3 of block `quad` point at
-    // dims 16e + 0, 4, 8, 12 of token 4*quad + k, so lane r receives dim 16e + r of tokens
-    // 4*quad .. +3: the depth slots in the order the score layout fixed.
-    typedef short v4i16 __attribute__((ext_vector_type(4)));
-    typedef v4i16 __attribute__((address_space(3))) * lds_v4i16_ptr;
-    const uint16_t *vlane = sv_cur + (4 * quad + (r >> 2)) * kVRow + 4 * (r & 3);
     uint2 va[8][kStepTiles];
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int t = 0; t < kStepTiles; ++t)
-            va[e][t] = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                                     (lds_v4i16_ptr)(vlane + t * kTileTokens * kVRow + 16 * e)));
-    if (MASKED) {
-#pragma unroll
-        for (int t = 0; t < kStepTiles; ++t) {
-            const int tok = t * kTileTokens + 4 * quad;
-            const uint32_t m01 = (tok < vlim_cur ? 0xffffu : 0u) | (tok + 1 < vlim_cur ? 0xffff0000u : 0u);
-            const uint32_t m23 = (tok + 2 < vlim_cur ? 0xffffu : 0u) | (tok + 3 < vlim_cur ? 0xffff0000u : 0u);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                va[e][t].x &= m01;
-                va[e][t].y &= m23;
-            }
-        }
-    }
+    read_v_operands<MASKED>(va, sv_cur, vlim_cur, quad, r);
 
     // scores of step next: the first kPreTiles tiles from operands read during the previous turn
     // (no LDS wait in front of the first MFMAs), the rest from LDS now; then the operands of the
@@ -209,31 +243,10 @@ __device__ inline void pipeline_turn(PrefillState (&st)[NG], float (&x)[NG][8], 
 #pragma unroll
     for (int t = 0; t < kPreTiles; ++t) read_k_tile(ka_pre[t], sk_next2 + t * kTileElems, quad, r);
 
-    // weights of step cur, rounded to bf16: the B operand of P.V as they stand
     bf16x8 pb[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const float m = st[g].m;
-        float pf[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pf[i] = __builtin_amdgcn_exp2f(x[g][i] - m);
-        const uint4 pw = {pack_bf16(pf[0], pf[1]), pack_bf16(pf[2], pf[3]), pack_bf16(pf[4], pf[5]),
-                          pack_bf16(pf[6], pf[7])};
-        pb[g] = __builtin_bit_cast(bf16x8, pw);
-    }
-
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint4 aw = {va[e][0].x, va[e][0].y, va[e][1].x, va[e][1].y};
-        const bf16x8 av = __builtin_bit_cast(bf16x8, aw);
-#pragma unroll
-        for (int g = 0; g < NG; ++g)
-            st[g].acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[g], st[g].acc[e], 0, 0, 0);
-    }
-    const uint4 one_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, one_bits);
-#pragma unroll
-    for (int g = 0; g < NG; ++g) st[g].lsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[g], st[g].lsum, 0, 0, 0);
+    for (int g = 0; g < NG; ++g) pb[g] = step_weights(x[g], st[g].m);
+    accumulate_pv<NG>(st, va, pb);
 
     float mx[NG];
 #pragma unroll
@@ -436,9 +449,9 @@ hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v
     const auto *vv = static_cast<const uint16_t *>(v_cache);
     auto *oo = static_cast<uint16_t *>(out);
     const int ng = p.heads_per_chunk;
+    const bool small = p.block_size < kTileTokens;
     const unsigned grid = unsigned(int64_t(p.num_q_heads / ng) * p.num_seqs * p.max_query_tiles);
     const dim3 g(grid), b(kThreads);
-    const bool small = p.block_size < kTileTokens;
     if (ng == 2 && !small) pa_prefill_mfma_kernel<2, false><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
     else if (ng == 2) pa_prefill_mfma_kernel<2, true><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
     else if (!small) pa_prefill_mfma_kernel<1, false><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
