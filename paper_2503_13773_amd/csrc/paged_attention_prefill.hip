@@ -117,8 +117,8 @@ __device__ inline void tile_scores(floatx4 (&s)[NG][kStepTiles], int t, const bf
     }
 }
 
-// Scaled (and, if MASKED, causally masked) scores of one head and their max over the step's
-// tokens.  The multiply also leaves canonical values, so the max tree compiles to bare
+// Scaled (and, if MASKED, causally masked) scores of one head and the max over this lane's 8
+// tokens of the step (the column's other 24 tokens sit in the lanes r + 16, r + 32, r + 48).  The multiply also leaves canonical values, so the max tree compiles to bare
 // v_max3/v_max without one quieting move per input.  `limit` = tokens of the step visible to
 // this lane's column (may be <= 0).
 template <bool MASKED>
@@ -131,17 +131,17 @@ __device__ inline float scale_mask_max(float (&x)[8], const floatx4 (&s)[kStepTi
             x[4 * t + i] = s[t][i] * scale_log2e;
             if (MASKED && t * kTileTokens + 4 * quad + i >= limit) x[4 * t + i] = -INFINITY;
         }
-    const float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    return max_over_quads(mx);
+    return fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
 }
 
 // Lazy rebase: the reference point m only moves when some column's max has grown by more than
 // 2^kLazyLog2 over it (always in the first step, m = -inf), so weights are at most 2^kLazyLog2
 // and the 36 multiplies of the rebase are rare.  Every column sees token 0 in its first step,
 // so m - m_new is never inf - inf.
-__device__ inline void rebase(PrefillState &st, float mx) {
-    if (__builtin_amdgcn_ballot_w64(mx > st.m + kLazyLog2) != 0) {
-        const float m_new = fmaxf(st.m, mx);
+__device__ inline void rebase(PrefillState &st, float lane_max) {
+    // the test needs no cross-lane max: if no lane holds a score above m + 2^kLazyLog2, none exists
+    if (__builtin_amdgcn_ballot_w64(lane_max > st.m + kLazyLog2) != 0) {
+        const float m_new = fmaxf(st.m, max_over_quads(lane_max));
         const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
         st.m = m_new;
 #pragma unroll
