@@ -161,3 +161,124 @@ def test_block_manager_with_reserved_pool():
         bm.release([99])
     with pytest.raises(ValueError):
         P.BlockManager(4, 5)
+
+
+# ---------------------------------------------------------------------------
+# seeded random sweeps against properties and small Python models of the same definitions
+# ---------------------------------------------------------------------------
+def test_allocation_properties_on_random_inputs():
+    import random
+    rnd = random.Random(11)
+    for _ in range(300):
+        n = rnd.randint(1, 12)
+        M = [rnd.choice([0, rnd.randint(1, 4000)]) for _ in range(n)]
+        RT = [rnd.uniform(0.01, 5.0) for _ in range(n)]
+        sp = [rnd.randint(1, 3000) for _ in range(n)]
+        A = rnd.randint(0, 12000)
+        alloc, slack = P.allocate(M, RT, sp, A)
+        assert all(0 <= a <= m for a, m in zip(alloc, M))            # never above the demand, nothing for M = 0
+        assert sum(alloc) <= A
+        if sum(M) <= A:
+            assert alloc == M and slack == A - sum(M)
+        else:
+            assert slack == -(sum(M) - A)
+            # the printed weights: share before the cap = floor(A w_i / sum w) over requests with a demand
+            live = [i for i in range(n) if M[i] > 0]
+            srt, ssp = sum(RT[i] for i in live), sum(sp[i] for i in live)
+            w = {i: RT[i] / srt * sp[i] / ssp for i in live}
+            sw = sum(w.values())
+            for i in live:
+                share = A * w[i] / sw
+                assert alloc[i] in (min(M[i], math.floor(share)), min(M[i], math.floor(share + 1e-9)),
+                                    min(M[i], math.floor(share - 1e-9)))
+
+
+def test_preemption_order_matches_a_sort_by_the_three_keys():
+    import bisect
+    import random
+    rnd = random.Random(12)
+    edges, width = (0.2, 0.5, 1.0), 64
+    for _ in range(200):
+        n = rnd.randint(0, 40)
+        slo = [rnd.choice([0.05, 0.2, 0.3, 0.5, 0.7, 1.0, 2.0]) for _ in range(n)]
+        rem = [rnd.randint(0, 600) for _ in range(n)]
+        occ = [rnd.randint(0, 50) for _ in range(n)]
+        want = sorted(range(n), key=lambda i: (-bisect.bisect_right(edges, slo[i]), -(rem[i] // width), occ[i], i))
+        assert P.preemption_order(slo, rem, occ, slo_edges=edges, token_bucket=width) == want
+
+
+def test_embedding_choice_matches_brute_force():
+    import random
+    rnd = random.Random(13)
+    for _ in range(300):
+        n = rnd.randint(0, 10)
+        a = [rnd.randint(0, 4000) for _ in range(n)]
+        u = [rnd.randint(0, x) for x in a]
+        sp_i, so_i, b = rnd.randint(1, 800), rnd.randint(1, 800), rnd.randint(0, 64)
+        fits = [j for j in range(n) if a[j] - (u[j] + so_i) - (sp_i + so_i) >= b]
+        got = P.embedding_choose(a, u, sp_i, so_i, b)
+        if not fits:
+            assert got is None
+        else:
+            best = min(fits, key=lambda j: (a[j] - u[j], j))
+            assert got == (best, a[best] - (u[best] + so_i) - b)
+
+
+def test_block_manager_against_a_set_model():
+    import random
+    rnd = random.Random(14)
+    for trial in range(20):
+        nb, res = rnd.randint(1, 60), 0
+        res = rnd.randint(0, nb)
+        bm = P.BlockManager(nb, res)
+        free_g, free_r, held = set(range(nb - res)), set(range(nb - res, nb)), []
+        for _ in range(200):
+            op = rnd.random()
+            if op < 0.45:
+                n = rnd.randint(0, 8)
+                got = bm.allocate(n)
+                if n <= len(free_g):
+                    want = sorted(free_g)[:n]
+                    assert got == want
+                    free_g -= set(want)
+                    held += want
+                else:
+                    assert got is None
+            elif op < 0.6:
+                n = rnd.randint(0, 4)
+                got = bm.allocate_reserved(n)
+                if n <= len(free_r):
+                    want = sorted(free_r)[:n]
+                    assert got == want
+                    free_r -= set(want)
+                    held += want
+                else:
+                    assert got is None
+            elif held:
+                k = rnd.randint(1, min(5, len(held)))
+                ids = rnd.sample(held, k)
+                bm.release(ids)
+                for i in ids:
+                    held.remove(i)
+                    (free_r if i >= nb - res else free_g).add(i)
+            assert (bm.free_general, bm.free_reserved) == (len(free_g), len(free_r))
+
+
+def test_padding_and_sweet_spot_properties():
+    import random
+    rnd = random.Random(15)
+    for _ in range(200):
+        rng_, c1, c2 = rnd.uniform(1, 500), rnd.uniform(0.0, 0.98), rnd.uniform(0.0, 0.98)
+        lo, hi = min(c1, c2), max(c1, c2)
+        assert P.padding(rng_, lo) <= P.padding(rng_, hi) + 1e-12          # more confidence, more padding
+        assert P.padding(2 * rng_, hi) == pytest.approx(2 * P.padding(rng_, hi), rel=1e-12)   # linear in the range
+        # the padding inverts the tail bound it comes from: exp(-2 t^2 / range^2) = 1 - c
+        t = P.padding(rng_, hi)
+        assert math.exp(-2 * t * t / (rng_ * rng_)) == pytest.approx(1 - hi, rel=1e-9)
+    for _ in range(100):
+        g, d = rnd.uniform(1e-4, 1e-2), rnd.uniform(0.0, 2.0)
+        a, b = rnd.uniform(1e-8, 1e-5), rnd.uniform(1.2, 2.2)
+        ss = P.sweet_spot(g, d, a, b, s_max=1e7)
+        if 0 < ss < math.inf:
+            assert a * ss ** b == pytest.approx(g * ss + d, rel=1e-6)      # the two regressors meet there
+            assert a * (2 * ss) ** b > g * (2 * ss) + d                     # recompute loses beyond it
