@@ -211,30 +211,6 @@ def main() -> int:
         f"event pairs | attention back-to-back {attn_region*1e6:.1f} us | copy avg {copy_avg*1e6:.1f} us, "
         f"back-to-back {copy_region*1e6:.1f} us")
 
-    # ---- GPU clocks under load, if rocm-smi is there: queried while attention launches keep the GPU busy ----
-    clocks = None
-    try:
-        import subprocess
-        proc = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
-                                stderr=subprocess.DEVNULL, text=True)
-        t_end = time.time() + 5.0
-        i = 0
-        while proc.poll() is None and time.time() < t_end:
-            for _ in range(50):
-                attn(reps[i % n_rep])
-                i += 1
-            torch.cuda.synchronize()
-        if proc.poll() is None:
-            proc.kill()
-        else:
-            raw = proc.stdout.read()
-            card = next(iter(json.loads(raw[raw.index("{"):]).values()))
-            clocks = {k.strip(": ").replace(" clock speed", ""): v.strip("()") for k, v in card.items()
-                      if "clock speed" in k}
-            log(f"[bench] clocks under load: {clocks}")
-    except Exception as e:  # the tool is optional
-        log(f"[bench] clocks not available ({type(e).__name__})")
-
     # ---- CPU baseline: the oracle as it stands, on the host cores, same inputs ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -315,7 +291,6 @@ def main() -> int:
             "attention_us_hot_same_replica": round(hot_med * 1e6, 2),
             "tokens_per_s": round(w.num_seqs / attn_avg, 1),
             "copy_us": round(copy_avg * 1e6, 2), "copy_GBs": round(copy_bytes / copy_avg / 1e9, 1),
-            "gpu_clocks_under_load": clocks,
         },
         "roofline": {"bound": "hbm", "kernel": {1: "pa_partial_valu_kernel", 2: "pa_partial_mfma_kernel", 3: "pa_partial_mfma_kernel", 4: "pa_stream_mfma_kernel"}[int(plan.kernel)],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
