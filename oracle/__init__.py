@@ -27,7 +27,8 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (about a second)."""
+    """Compile the oracle with gcc (about a second) when the library is missing or older than
+    its source.  Starts a child process: call it before anything in the process touches the GPU."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
                                "-o", _LIB, _SRC, "-lm"])
@@ -37,7 +38,8 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # an existing library is loaded as it is; only a missing one is compiled here
+        lib = ctypes.CDLL(_LIB if os.path.exists(_LIB) else build())
         lib.oracle_paged_attention_decode.restype = ctypes.c_int
         lib.oracle_paged_attention_decode.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
