@@ -138,11 +138,12 @@ def test_swap_out_poison_swap_in_round_trip(oracle_mod, full):
               tables=torch.from_numpy(sp["tables_after"]).cuda())
     after = out_bits(run_gpu(w, d2))
     assert np.array_equal(before, after)
-    rows = [(v, 3) for v in sp["victims"][:4]]
+    # every element of the post-swap attention against the oracle on the post-swap host pools
     ref = oracle_mod.paged_attention_decode(w.q, h1[0], h1[1], sp["tables_after"], w.context_lens,
-                                            w.scale, dtype="bf16", rows=rows, num_threads=4)
+                                            w.scale, dtype="bf16", num_threads=8)
     got = run_gpu(w, d2).float().cpu().numpy().astype(np.float64)
-    assert max(np.abs(got[s_, h] - ref[s_, h]).max() for s_, h in rows) <= 2e-2
+    assert np.isfinite(ref).all() and np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= 2e-2
 
 
 def test_swap_to_pinned_host_memory_and_back(oracle_mod):
