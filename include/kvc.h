@@ -151,6 +151,29 @@ KVC_API int kvc_paged_attention_decode_merge(const int32_t *context_lens, void *
                                      const kvc_attn_desc *desc, void *workspace,
                                      size_t workspace_bytes, void *hip_stream);
 
+/*
+ * kvc_paged_attention_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, checks, kernels and results as kvc_paged_attention_decode, but
+ * the split-K workspace is a fixed region of KVC_NOALLOC_WORKSPACE_BYTES that the library
+ * holds on every GPU it is loaded on (placed with the code object, kept until the process
+ * ends).  The call allocates and frees nothing.
+ *   - A descriptor whose kvc_paged_attention_decode_workspace_bytes exceeds
+ *     KVC_NOALLOC_WORKSPACE_BYTES is refused with KVC_ERR_WORKSPACE (nothing is launched);
+ *     a tight desc->max_context_len keeps the need small.
+ *   - The device that owns `hip_stream` must be the current device.  The first call on a
+ *     device looks up the region's address (a HIP symbol query); make that call outside a
+ *     graph capture.
+ *   - All calls on one GPU share the region: calls whose kernels can overlap in time (different
+ *     streams, or graphs replayed concurrently) race and give undefined results.  Calls on one
+ *     stream are ordered and safe.
+ */
+#define KVC_NOALLOC_WORKSPACE_BYTES (64u << 20)
+KVC_API int kvc_paged_attention_decode_noalloc(const void *q, const void *k_cache, const void *v_cache,
+                                               const int32_t *block_tables, const int32_t *context_lens,
+                                               float scale, void *out, const kvc_attn_desc *desc,
+                                               void *hip_stream);
+
 /* Blocking check of the device index arrays against `desc`: 0 <= context_lens[n] <=
  * min(max_context_len, max_blocks_per_seq * block_size) and every dereferenced table entry in
  * [0, num_pool_blocks).  Returns KVC_ERR_BAD_INDEX on the first violation. */

@@ -71,6 +71,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp, sz, vp]
+    L.kvc_paged_attention_decode_noalloc.restype = ctypes.c_int
+    L.kvc_paged_attention_decode_noalloc.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp]
     L.kvc_paged_attention_decode_merge.restype = ctypes.c_int
     L.kvc_paged_attention_decode_merge.argtypes = [i32p, vp, dp, vp, sz, vp]
     L.kvc_validate_attention_inputs.restype = ctypes.c_int
@@ -152,6 +154,8 @@ def _attn_args(q, k_cache, v_cache, block_tables, context_lens, out, desc, works
         out = torch.empty_like(q)
     elif out.shape != q.shape or out.dtype != q.dtype or not out.is_cuda or not out.is_contiguous():
         raise ValueError("out must look like q")
+    if workspace is False:          # the call brings its own workspace
+        return out, None, None, 0
     need = workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -174,6 +178,23 @@ def paged_attention_decode(q, k_cache, v_cache, block_tables, context_lens, scal
         q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
         context_lens.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc), ws_ptr, ws_len,
         _stream_handle(stream)), "kvc_paged_attention_decode")
+    return out
+
+
+NOALLOC_WORKSPACE_BYTES = 64 << 20
+
+
+def paged_attention_decode_noalloc(q, k_cache, v_cache, block_tables, context_lens, scale: float,
+                                   out, desc: AttnDesc, stream=None):
+    """kvc_paged_attention_decode_noalloc: the caller passes `out`; nothing is allocated here or
+    in the library (the workspace is the library's own fixed per-GPU region)."""
+    if out is None:
+        raise ValueError("out is required")
+    _attn_args(q, k_cache, v_cache, block_tables, context_lens, out, desc, workspace=False)
+    _check(lib().kvc_paged_attention_decode_noalloc(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
+        context_lens.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc),
+        _stream_handle(stream)), "kvc_paged_attention_decode_noalloc")
     return out
 
 

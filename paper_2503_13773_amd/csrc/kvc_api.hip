@@ -3,13 +3,42 @@
 #include <math.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "kvc_internal.h"
 
+// Workspace of kvc_paged_attention_decode_noalloc: one copy per GPU, placed by the loader with the
+// code object and held until the process ends.  In host code the name below is only a handle
+// for hipGetSymbolAddress; the address kernels can use is looked up once per device.
+constexpr size_t kScratchBytes = size_t(KVC_NOALLOC_WORKSPACE_BYTES);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+hipError_t scratch_of_current_device(void **ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 int hip_failed(hipError_t e) {
     g_last_hip_error = int(e);
@@ -318,6 +347,29 @@ int kvc_paged_attention_decode(const void *q, const void *k_cache, const void *v
     if (rc != KVC_OK) return rc;
     kvc::Workspace ws;
     rc = check_workspace(pl, workspace, workspace_bytes, &ws);
+    if (rc != KVC_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = run_partial(q, k_cache, v_cache, block_tables, context_lens, scale, out, desc, pl, ws, stream);
+    if (rc != KVC_OK) return rc;
+    return run_merge(context_lens, out, desc, pl, ws, stream);
+}
+
+int kvc_paged_attention_decode_noalloc(const void *q, const void *k_cache, const void *v_cache,
+                                       const int32_t *block_tables, const int32_t *context_lens,
+                                       float scale, void *out, const kvc_attn_desc *desc,
+                                       void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    if (pl.workspace_bytes > kScratchBytes) return KVC_ERR_WORKSPACE;
+    if (desc->num_seqs == 0) return KVC_OK;
+    rc = check_attn_args(q, k_cache, v_cache, block_tables, context_lens, scale, out);
+    if (rc != KVC_OK) return rc;
+    void *base = nullptr;
+    const hipError_t e = scratch_of_current_device(&base);
+    if (e != hipSuccess) return hip_failed(e);
+    kvc::Workspace ws;
+    rc = check_workspace(pl, base, kScratchBytes, &ws);
     if (rc != KVC_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     rc = run_partial(q, k_cache, v_cache, block_tables, context_lens, scale, out, desc, pl, ws, stream);
