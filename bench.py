@@ -2,16 +2,20 @@
 """Benchmark of the paged-KV decode hot path on one MI355X.
 
 A step = one pass of the whole hot path over one synthetic batch, all inputs resident in
-HBM: paged_attention_decode (split-K partial kernel + merge kernel) over the batch, then
-kv_block_copy swapping the K and V blocks of 20 % of the batch's sequences out to a second
+HBM: paged_attention_decode over the batch (with the balanced kernel one launch: split
+contexts are merged by the last wavefront to arrive), then kv_block_copy swapping the K and V blocks of 20 % of the batch's sequences out to a second
 device pool.  Successive steps rotate over replicas of the KV pools at different addresses
 (>= 2 GiB in total), the way successive layers of a model each own a KV pool, so that the
 256 MB memory-side cache cannot serve the KV reads.  Block tables, context lengths and the
 copy mapping are shared by the replicas, as they are shared by the layers of one decode step.
 
+Before anything is timed the step's results are checked: attention rows against the CPU
+oracle and the swapped-out blocks bit for bit; a mismatch ends the run with exit status 4.
+
 Prints ONE JSON line: whole-step throughput in algorithmic GB/s, the roofline record of the
-dominant kernel (the attention partial kernel, timed per launch with HIP events on the
-launch stream) and the CPU oracle's throughput on the host cores as a baseline.
+dominant kernel (the attention kernel, timed per launch with HIP events on the launch
+stream; with the balanced kernel that launch is the whole paged_attention_decode call) and
+the CPU oracle's throughput on the host cores as a baseline.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3b] ...
 """
@@ -57,6 +61,7 @@ def main() -> int:
                     help="rotate over replicas of the batch totalling at least this many KV bytes")
     ap.add_argument("--swap-frac", type=float, default=0.20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true", help="skip the oracle check before timing (A/B timing runs)")
     ap.add_argument("--cpu-threads", type=int, default=0)
     args = ap.parse_args()
 
@@ -66,6 +71,12 @@ def main() -> int:
         return 2
 
     import numpy as np
+
+    oracle = None
+    if not (args.no_cpu_baseline and args.no_check):
+        import oracle          # test infrastructure: the check before timing and the cpu_baseline leg only
+        oracle.build()         # compiles only when missing or stale, and before the GPU is touched
+
     import torch
 
     import kvc_workloads as W
@@ -115,7 +126,7 @@ def main() -> int:
         rep = dict(pool1=pool1, k=pool1[0], v=pool1[1],
                    q=base["q"].clone(), tables=base["tables"], lens=base["lens"],
                    mapping=base["mapping"], out=torch.empty_like(base["q"]),
-                   ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda"),
+                   ws=K.new_workspace(desc),
                    pool2=torch.zeros((2, pool2_blocks) + tuple(pool1.shape[2:]), dtype=pool1.dtype,
                                      device="cuda"))
         rep["src_pool"] = K.pool_of(rep["pool1"])
@@ -152,9 +163,32 @@ def main() -> int:
         attn(rep)
         copy(rep)
 
-    # ---- correctness guard: one replica against a few oracle rows (cheap) ----
-    step(reps[-1])
+    # ---- check before timing: every replica runs one step; attention rows of the first and
+    # last replica against the oracle, the swapped-out blocks of the last bit for bit ----
+    for rep in reps:
+        step(rep)
     torch.cuda.synchronize()
+    if not args.no_check:
+        crng = np.random.default_rng(99)
+        order = np.argsort(w.context_lens)
+        seqs = sorted(set(int(x) for x in order[:2]) | set(int(x) for x in order[-2:]) |
+                      set(int(x) for x in crng.integers(0, w.num_seqs, 12)))
+        rows = [(sq, h) for sq in seqs for h in range(w.num_q_heads)]
+        ref = oracle.attention_of_workload(w, rows=rows, num_threads=min(8, os.cpu_count() or 1))
+        for rep in (reps[0], reps[-1]):
+            got = rep["out"].float().cpu().numpy().astype(np.float64)
+            err = max(float(np.abs(got[sq, h] - ref[sq, h]).max()) for sq, h in rows)
+            if not (err <= 2e-2):
+                print(f"bench.py: attention differs from the oracle (max abs err {err:.3e} > 2e-2)", file=sys.stderr)
+                return 4
+        want2 = np.zeros((2, pool2_blocks) + pool_np.shape[2:], dtype=np.uint16)
+        oracle.kv_block_copy(pool_np, want2, mapping_np)
+        got2 = reps[-1]["pool2"].view(torch.int16).cpu().numpy().view(np.uint16)
+        if not np.array_equal(got2, want2):
+            print("bench.py: swapped-out blocks differ from the oracle copy", file=sys.stderr)
+            return 4
+        log(f"[bench] check before timing: {len(rows)} attention rows within 2e-2 of the oracle (max abs err {err:.2e}), "
+            f"{len(src_ids)} swapped blocks bit-exact")
 
     def timed_wall(fn, steps, warmup):
         for i in range(warmup):
@@ -214,7 +248,6 @@ def main() -> int:
     # ---- CPU baseline: the oracle as it stands, on the host cores, same inputs ----
     cpu = None
     if not args.no_cpu_baseline:
-        import oracle
         threads = args.cpu_threads or min(oracle.num_threads_available(), os.cpu_count() or 1)
         h2 = np.zeros((2, pool2_blocks) + pool_np.shape[2:], dtype=np.uint16)
         # bounded sample: whole steps of the same batch, repeated until ~10 s of CPU time
@@ -262,7 +295,7 @@ def main() -> int:
         except Exception:
             traffic = None
 
-    part_bytes = attn_bytes  # what one partial-kernel launch must move (K+V once, q, out/partials not counted)
+    part_bytes = attn_bytes  # what one launch of the attention kernel must move (K+V once, q, out; partials not counted)
     achieved = part_bytes / part_avg / 1e9
     value = step_bytes / step_s / 1e9
     result = {
@@ -274,7 +307,7 @@ def main() -> int:
                    "head_dim": w.head_dim, "block_size": w.block_size,
                    "mean_context_len": round(float(w.context_lens.mean()), 1),
                    "max_context_len": w.max_context_len,
-                   "step": "paged_attention_decode (partial+merge) + kv_block_copy swap-out of "
+                   "step": "paged_attention_decode (" + ("one launch" if plan.merge_grid == 0 else "partial + merge launches") + ") + kv_block_copy swap-out of "
                            f"{len(victims)} sequences ({len(src_ids)} blocks, K and V planes)",
                    "replicas": n_rep, "kernel": int(plan.kernel),
                    "partition_tokens": int(plan.partition_tokens)},
@@ -295,7 +328,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": {1: "pa_partial_valu_kernel", 2: "pa_partial_mfma_kernel", 3: "pa_partial_mfma_kernel", 4: "pa_stream_mfma_kernel"}[int(plan.kernel)],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "bytes_per_launch": int(part_bytes), "avg_launch_us": round(part_avg * 1e6, 2)},
+                     "bytes_per_launch": int(part_bytes), "avg_launch_us": round(part_avg * 1e6, 2),
+                     "covers": "whole paged_attention_decode call" if plan.merge_grid == 0 else "partial kernel only (a merge launch follows)"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)

@@ -97,7 +97,8 @@ typedef struct {
 typedef struct {
     int32_t kernel;            /* the kvc_kernel that will run (never AUTO) */
     int32_t partition_tokens;
-    int32_t max_partitions;    /* partitions per sequence the grid provides for */
+    int32_t max_partitions;    /* partitions per sequence the grid provides for (balanced kernel:
+                                  partial slots per wavefront) */
     int32_t partial_grid;      /* workgroups of the partial kernel */
     int32_t merge_grid;        /* workgroups of the merge kernel (0: not launched) */
     int32_t reserved;
@@ -113,7 +114,8 @@ KVC_API int kvc_last_hip_error(void);
 KVC_API int kvc_attn_plan(const kvc_attn_desc *desc, kvc_attn_plan_info *plan);
 
 /* Bytes of device workspace kvc_paged_attention_decode needs for `desc`
- * (0 when no sequence can span more than one partition, or on a bad desc). */
+ * (0 when no sequence can span more than one partition, or on a bad desc).  For the balanced
+ * kernel it depends on the group size only, not on the batch or the context lengths. */
 KVC_API size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *desc);
 
 /*
@@ -128,11 +130,17 @@ KVC_API size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *d
  *     is fine).  One block id may appear in many rows (shared prefix).
  *   - context_lens[n] == 0 writes a row of zeros.
  *   - Accumulation is fp32; bf16 output is rounded to nearest even.
- *   - Two launches: a split-K partial kernel over pieces of each (sequence, kv head) context
- *     and a merge kernel; a context that is not split is finished by the first.
+ *   - Split-K: a long context is cut into pieces whose (max, sum, accumulator) partials go
+ *     through the workspace.  The balanced kernel (KVC_KERNEL_MFMA_BALANCED, what AUTO picks for
+ *     bf16 / head_dim 128) is ONE launch: the last wavefront to finish a piece of a cut context
+ *     merges its partials and writes the row.  The other kernels are followed by a merge launch.
  *   - `workspace`: device memory, 256-byte aligned, at least
- *     kvc_paged_attention_decode_workspace_bytes(desc); may be NULL when that is 0.  It is
- *     scratch: contents before and after the call are meaningless.
+ *     kvc_paged_attention_decode_workspace_bytes(desc); may be NULL when that is 0.  Its first
+ *     4096 bytes hold arrival counters that must be 0 when a call starts:
+ *     kvc_paged_attention_decode_workspace_init sets them once after allocation, every call
+ *     leaves them 0 again (whatever descriptor it ran with), and no call writes anything else
+ *     there.  The rest is scratch: contents before and after a call are meaningless.  Calls that
+ *     share a workspace must not overlap in time (one stream, or ordered by events).
  *   - q, k_cache, v_cache, out must be 16-byte aligned.
  */
 KVC_API int kvc_paged_attention_decode(const void *q, const void *k_cache, const void *v_cache,
@@ -140,9 +148,16 @@ KVC_API int kvc_paged_attention_decode(const void *q, const void *k_cache, const
                                float scale, void *out, const kvc_attn_desc *desc,
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* The two launches of kvc_paged_attention_decode on their own (same arguments, same
- * checks), for callers that time or schedule them separately.  Running partial then
- * merge on one stream equals kvc_paged_attention_decode. */
+/* Prepares a freshly allocated (or overwritten) workspace: sets its 4096-byte counter header
+ * to 0 with a small kernel on `hip_stream` (no memset node, safe under graph capture).
+ * workspace_bytes == 0 is a no-op. */
+KVC_API int kvc_paged_attention_decode_workspace_init(void *workspace, size_t workspace_bytes,
+                                                      void *hip_stream);
+
+/* The launches of kvc_paged_attention_decode on their own (same arguments, same checks), for
+ * callers that time or schedule them separately.  Running partial then merge on one stream
+ * equals kvc_paged_attention_decode; with the balanced kernel partial is the whole call and
+ * merge launches nothing. */
 KVC_API int kvc_paged_attention_decode_partial(const void *q, const void *k_cache, const void *v_cache,
                                        const int32_t *block_tables, const int32_t *context_lens,
                                        float scale, void *out, const kvc_attn_desc *desc,
@@ -160,15 +175,16 @@ KVC_API int kvc_paged_attention_decode_merge(const int32_t *context_lens, void *
  * ends).  The call allocates and frees nothing.
  *   - A descriptor whose kvc_paged_attention_decode_workspace_bytes exceeds
  *     KVC_NOALLOC_WORKSPACE_BYTES is refused with KVC_ERR_WORKSPACE (nothing is launched);
- *     a tight desc->max_context_len keeps the need small.
+ *     every descriptor the balanced kernel serves fits.
  *   - The device that owns `hip_stream` must be the current device.  The first call on a
  *     device looks up the region's address (a HIP symbol query); make that call outside a
  *     graph capture.
  *   - All calls on one GPU share the region: calls whose kernels can overlap in time (different
  *     streams, or graphs replayed concurrently) race and give undefined results.  Calls on one
- *     stream are ordered and safe.
+ *     stream are ordered and safe.  The region starts zeroed and every call leaves its counter
+ *     header zeroed, so no initialisation call is needed.
  */
-#define KVC_NOALLOC_WORKSPACE_BYTES (64u << 20)
+#define KVC_NOALLOC_WORKSPACE_BYTES (32u << 20)
 KVC_API int kvc_paged_attention_decode_noalloc(const void *q, const void *k_cache, const void *v_cache,
                                                const int32_t *block_tables, const int32_t *context_lens,
                                                float scale, void *out, const kvc_attn_desc *desc,

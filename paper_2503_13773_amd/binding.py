@@ -71,6 +71,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp, sz, vp]
+    L.kvc_paged_attention_decode_workspace_init.restype = ctypes.c_int
+    L.kvc_paged_attention_decode_workspace_init.argtypes = [vp, sz, vp]
     L.kvc_paged_attention_decode_noalloc.restype = ctypes.c_int
     L.kvc_paged_attention_decode_noalloc.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp]
     L.kvc_paged_attention_decode_merge.restype = ctypes.c_int
@@ -140,6 +142,23 @@ def workspace_bytes(desc: AttnDesc) -> int:
     return int(lib().kvc_paged_attention_decode_workspace_bytes(ctypes.byref(desc)))
 
 
+def workspace_init(workspace, stream=None) -> None:
+    """Zero the counter header of a workspace tensor (needed once after allocation)."""
+    _check(lib().kvc_paged_attention_decode_workspace_init(
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+        "kvc_paged_attention_decode_workspace_init")
+
+
+def new_workspace(desc: AttnDesc, device="cuda", stream=None):
+    """Allocate a workspace for `desc` and prepare it (None when the descriptor needs none)."""
+    need = workspace_bytes(desc)
+    if not need:
+        return None
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
 def _attn_args(q, k_cache, v_cache, block_tables, context_lens, out, desc, workspace):
     for t in (q, k_cache, v_cache, block_tables, context_lens):
         if not t.is_cuda or not t.is_contiguous():
@@ -158,7 +177,7 @@ def _attn_args(q, k_cache, v_cache, block_tables, context_lens, out, desc, works
         return out, None, None, 0
     need = workspace_bytes(desc)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = new_workspace(desc, q.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     return out, workspace, ws_ptr, ws_len
@@ -181,7 +200,7 @@ def paged_attention_decode(q, k_cache, v_cache, block_tables, context_lens, scal
     return out
 
 
-NOALLOC_WORKSPACE_BYTES = 64 << 20
+NOALLOC_WORKSPACE_BYTES = 32 << 20
 
 
 def paged_attention_decode_noalloc(q, k_cache, v_cache, block_tables, context_lens, scale: float,

@@ -17,8 +17,12 @@ SOURCES = ["kvc_api.hip", "kv_block_copy.hip", "kv_cache_append.hip", "paged_att
            "paged_attention_mfma.hip", "paged_attention_mfma_stream.hip", "paged_attention_prefill.hip",
            "paged_attention_merge.hip"]
 # packed-fp32 instructions are switched off on purpose for this target
+# The atomic optimizer is switched off: it rewrites an atomic add issued by one lane into a
+# wavefront-wide reduction that reads the result back at once, which makes the balanced
+# attention kernel wait for its arrival counters instead of consuming tiles meanwhile.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

@@ -60,8 +60,8 @@ struct Plan {
     int max_partitions;
     int64_t partial_grid;
     int64_t merge_grid;
-    uint64_t ml_offset;   // offset of the (max, sum) array inside the workspace
-    uint64_t cnt_offset;  // offset of the per-row partial counts (balanced kernel)
+    uint64_t acc_offset;  // offset of the accumulator array inside the workspace (after the counter header)
+    uint64_t ml_offset;   // offset of the (max, sum) array
     uint64_t workspace_bytes;
     int min_chunk_tiles;
     int max_context_len;
@@ -108,24 +108,26 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
     if (kernel == KVC_KERNEL_MFMA_BALANCED && !balanced_ok(*d, max_ctx)) return KVC_ERR_UNSUPPORTED;
 
     const int64_t rows = int64_t(d->num_seqs) * d->num_q_heads;
+    constexpr uint64_t kHeader = kvc::kWorkspaceHeaderBytes;
     if (kernel == KVC_KERNEL_MFMA_BALANCED) {
-        // A wavefront never takes fewer than min_chunk tiles, which bounds the partials of a row
-        // (and the workspace) from the host.
+        // One launch: cut rows are merged by the last worker to arrive.  A wavefront never takes
+        // fewer than min_chunk tiles; the workspace is two partial slots per wavefront.
         const int64_t max_tiles = ceil_div(max_ctx, 16);
         const int min_chunk = d->partition_tokens ? d->partition_tokens / 16
                                                   : int(std::max<int64_t>(4, ceil_div(max_tiles, 32)));
-        const int64_t parts = ceil_div(max_tiles, min_chunk) + 1;
+        const int group = d->num_q_heads / d->num_kv_heads;
+        const uint64_t slots = uint64_t(kvc::kNumCUs) * kvc::kWaves * 2;
         pl->kernel = kernel;
         pl->partition_tokens = min_chunk * 16;
         pl->min_chunk_tiles = min_chunk;
-        pl->max_partitions = int(parts);
+        pl->max_partitions = 2;           // partial slots per worker
         pl->partial_grid = kvc::kNumCUs;  // 4 wavefronts per CU: one worker per SIMD
-        pl->merge_grid = ceil_div(rows, kvc::kWaves);
+        pl->merge_grid = 0;
         pl->max_context_len = max_ctx;
-        const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);
-        pl->ml_offset = (acc + 255) & ~uint64_t(255);
-        pl->cnt_offset = (pl->ml_offset + uint64_t(rows) * parts * 2 * sizeof(float) + 255) & ~uint64_t(255);
-        pl->workspace_bytes = pl->cnt_offset + uint64_t(d->num_seqs) * d->num_kv_heads * sizeof(int32_t);
+        const uint64_t acc = slots * group * d->head_dim * sizeof(float);
+        pl->acc_offset = kHeader;
+        pl->ml_offset = (kHeader + acc + 255) & ~uint64_t(255);
+        pl->workspace_bytes = pl->ml_offset + slots * group * 2 * sizeof(float);
         return KVC_OK;
     }
 
@@ -154,10 +156,10 @@ int make_plan(const kvc_attn_desc *d, Plan *pl) {
     pl->merge_grid = parts > 1 ? ceil_div(rows, kvc::kWaves) : 0;
     pl->max_context_len = max_ctx;
     pl->min_chunk_tiles = 0;
-    pl->cnt_offset = 0;
+    pl->acc_offset = kHeader;
     if (parts > 1) {
         const uint64_t acc = uint64_t(rows) * parts * d->head_dim * sizeof(float);
-        pl->ml_offset = (acc + 255) & ~uint64_t(255);
+        pl->ml_offset = (kHeader + acc + 255) & ~uint64_t(255);
         pl->workspace_bytes = pl->ml_offset + uint64_t(rows) * parts * 2 * sizeof(float);
     } else {
         pl->ml_offset = 0;
@@ -179,6 +181,7 @@ kvc::AttnParams make_params(const kvc_attn_desc &d, const Plan &pl, float scale)
     p.max_partitions = pl.max_partitions;
     p.k_via_lds = pl.kernel == KVC_KERNEL_MFMA_LDS;
     p.min_chunk_tiles = pl.min_chunk_tiles;
+    p.max_context_len = pl.max_context_len;
     p.scale = scale;
     p.scale_log2e = float(double(scale) * 1.4426950408889634);
     return p;
@@ -191,9 +194,10 @@ int check_workspace(const Plan &pl, void *workspace, size_t workspace_bytes, kvc
     if (pl.workspace_bytes == 0) return KVC_OK;
     if (!workspace || workspace_bytes < pl.workspace_bytes) return KVC_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
-    ws->acc = static_cast<float *>(workspace);
-    ws->ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
-    ws->cnt = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(workspace) + pl.cnt_offset);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    ws->cnt = reinterpret_cast<int32_t *>(base);
+    ws->acc = reinterpret_cast<float *>(base + pl.acc_offset);
+    ws->ml = reinterpret_cast<float *>(base + pl.ml_offset);
     return KVC_OK;
 }
 
@@ -219,9 +223,7 @@ int run_merge(const int32_t *context_lens, void *out, const kvc_attn_desc *desc,
     if (pl.merge_grid == 0) return KVC_OK;
     const kvc::AttnParams p = make_params(*desc, pl, 1.0f);
     const hipError_t e = kvc::launch_merge(context_lens, out, ws, p, desc->dtype, desc->head_dim,
-                                           pl.kernel != KVC_KERNEL_VALU,
-                                           pl.kernel == KVC_KERNEL_MFMA_BALANCED, int(pl.merge_grid),
-                                           stream);
+                                           pl.kernel != KVC_KERNEL_VALU, int(pl.merge_grid), stream);
     return e == hipSuccess ? KVC_OK : hip_failed(e);
 }
 
@@ -262,7 +264,7 @@ int check_pools(const kvc_pool *src, const kvc_pool *dst, const int64_t *mapping
 
 extern "C" {
 
-int kvc_version(void) { return 100; }
+int kvc_version(void) { return 200; }
 
 const char *kvc_status_string(int status) {
     switch (status) {
@@ -301,6 +303,14 @@ int kvc_attn_plan(const kvc_attn_desc *desc, kvc_attn_plan_info *plan) {
 size_t kvc_paged_attention_decode_workspace_bytes(const kvc_attn_desc *desc) {
     Plan pl;
     return make_plan(desc, &pl) == KVC_OK ? size_t(pl.workspace_bytes) : 0;
+}
+
+int kvc_paged_attention_decode_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (workspace_bytes == 0) return KVC_OK;
+    if (!workspace || workspace_bytes < kvc::kWorkspaceHeaderBytes) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
+    const hipError_t e = kvc::launch_workspace_init(workspace, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
 }
 
 int kvc_paged_attention_decode_partial(const void *q, const void *k_cache, const void *v_cache,
@@ -426,6 +436,7 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
         vp.num_seqs = total_q;
         vp.partition_tokens = 1 << 30;
         vp.max_partitions = 1;
+        vp.max_context_len = desc->max_blocks_per_seq * desc->block_size;
         const int64_t grid = int64_t(total_q) * (desc->num_q_heads / kvc::valu_head_chunk(vp.group));
         if (grid > kMaxGrid) return KVC_ERR_BAD_SHAPE;
         const hipError_t e = kvc::launch_prefill_valu(q, k_cache, v_cache, block_tables, context_lens, q_start,

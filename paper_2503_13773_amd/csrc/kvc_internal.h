@@ -21,6 +21,7 @@ struct AttnParams {
     int max_partitions;     // partitions per sequence the grid and workspace provide for
     int k_via_lds;          // MFMA kernel: stage K tiles through LDS (1) or load them in operand layout (0)
     int min_chunk_tiles;    // balanced kernel: smallest number of 16-token tiles a worker takes
+    int max_context_len;    // context lengths are clamped to this (the bound every size is derived from)
     float scale;            // as given by the caller
     float scale_log2e;      // scale * log2(e), for the base-2 softmax of the MFMA kernel
 };
@@ -40,15 +41,18 @@ struct PrefillParams {
     float scale_log2e;
 };
 
-// Workspace layout: acc [num_seqs][num_q_heads][max_partitions][head_dim] fp32, then
-// ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum), then
-// (balanced kernel only) cnt [num_seqs][num_kv_heads] int32 = partials per row; each array
-// starts at a 256-byte aligned offset.
+// Workspace layout.  The first kWorkspaceHeaderBytes hold the arrival counters of the
+// balanced kernel (int32 [workers], 0 between calls); no kernel writes anything else there.
+// Fixed-partition kernels: acc [num_seqs][num_q_heads][max_partitions][head_dim] fp32, then
+// ml [num_seqs][num_q_heads][max_partitions][2] fp32 (running max, running sum).
+// Balanced kernel: acc [workers][2][group][head_dim] fp32, ml [workers][2][group][2] fp32
+// (two partial slots per worker).  Each array starts at a 256-byte aligned offset.
 struct Workspace {
     float *acc;
     float *ml;
     int32_t *cnt;
 };
+constexpr size_t kWorkspaceHeaderBytes = 4096;
 
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup, every attention kernel
 constexpr int kWaves = kThreads / 64;
@@ -68,11 +72,11 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
                                       const int32_t *block_tables, const int32_t *context_lens,
                                       void *out, Workspace ws, const AttnParams &p, int grid,
                                       hipStream_t stream);
-// base2: partials are in base-2 units; counted: partial counts come from ws.cnt (balanced
-// kernel) instead of ceil(context_len / partition_tokens).
+// base2: partials are in base-2 units.
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
-                        int dtype, int head_dim, bool base2, bool counted, int grid,
-                        hipStream_t stream);
+                        int dtype, int head_dim, bool base2, int grid, hipStream_t stream);
+// Sets the counter header of a workspace to 0 (a fill kernel, safe under graph capture).
+hipError_t launch_workspace_init(void *workspace, hipStream_t stream);
 hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens,
                                const int32_t *q_start, void *out, const PrefillParams &p,

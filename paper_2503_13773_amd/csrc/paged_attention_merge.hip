@@ -11,10 +11,9 @@
 // memory round trips deep.  The accumulator rows are then streamed with the weight broadcast
 // from its lane, lanes striding over head_dim (coalesced 256/512-byte reads, 8 rows in flight).
 //
-// The number of partials of a row is ceil(context_len / partition_tokens) for the
-// fixed-partition kernels, or the count the balanced kernel left in the workspace.  Rows
-// finished by the partial kernel (one partial) are skipped; with the balanced kernel, rows
-// with an empty context are zeroed here.
+// The number of partials of a row is ceil(context_len / partition_tokens); rows finished by
+// the partial kernel (one partial, or an empty context) are skipped.  The balanced kernel
+// merges inside its own launch and does not use this one.
 #include <math.h>
 
 #include "kvc_internal.h"
@@ -32,7 +31,7 @@ __device__ inline uint16_t f32_to_bf16_rne(float x) {
 __device__ inline void store_out(float *o, float x) { *o = x; }
 __device__ inline void store_out(uint16_t *o, float x) { *o = f32_to_bf16_rne(x); }
 
-template <typename T, int D, bool BASE2, bool COUNTED>
+template <typename T, int D, bool BASE2>
 __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__restrict__ context_lens,
                                                             T *__restrict__ out, Workspace ws,
                                                             AttnParams p) {
@@ -45,22 +44,12 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
     const float *ml = ws.ml + size_t(row) * p.max_partitions * 2;
     const float *acc = ws.acc + size_t(row) * p.max_partitions * D + lane * DPL;
 
-    // Three independent loads go out together: the context length, the partial count and
-    // (speculatively, whatever the slots hold) the (max, sum) pairs of the first 64 slots.
-    const int ctx = context_lens[seq];
-    int nparts = COUNTED ? ws.cnt[seq * p.num_kv_heads + head / p.group] : 0;
+    // Two independent loads go out together: the context length and (speculatively, whatever
+    // the slots hold) the (max, sum) pairs of the first 64 slots.
+    const int ctx = min(context_lens[seq], p.max_context_len);
     float2 ml0 = float2{-INFINITY, 0.f};
     if (lane < p.max_partitions) ml0 = *reinterpret_cast<const float2 *>(ml + 2 * lane);
-
-    if (COUNTED) {
-        if (ctx <= 0) {
-#pragma unroll
-            for (int j = 0; j < DPL; ++j) store_out(out + size_t(row) * D + lane * DPL + j, 0.f);
-            return;
-        }
-    } else {
-        nparts = (ctx + p.partition_tokens - 1) / p.partition_tokens;  // <= 1: finished already, or empty
-    }
+    int nparts = (ctx + p.partition_tokens - 1) / p.partition_tokens;  // <= 1: finished already, or empty
     if (nparts <= 1) return;
     nparts = min(nparts, p.max_partitions);
 
@@ -109,30 +98,37 @@ __global__ __launch_bounds__(kThreads) void pa_merge_kernel(const int32_t *__res
 }
 
 template <typename T, int D>
-void launch(bool base2, bool counted, const int32_t *cl, void *out, Workspace ws, const AttnParams &p,
-            int grid, hipStream_t stream) {
+void launch(bool base2, const int32_t *cl, void *out, Workspace ws, const AttnParams &p, int grid,
+            hipStream_t stream) {
     T *o = static_cast<T *>(out);
     const dim3 g(grid), b(kThreads);
-    if (counted)
-        pa_merge_kernel<T, D, true, true><<<g, b, 0, stream>>>(cl, o, ws, p);  // balanced kernel: always base 2
-    else if (base2)
-        pa_merge_kernel<T, D, true, false><<<g, b, 0, stream>>>(cl, o, ws, p);
+    if (base2)
+        pa_merge_kernel<T, D, true><<<g, b, 0, stream>>>(cl, o, ws, p);
     else
-        pa_merge_kernel<T, D, false, false><<<g, b, 0, stream>>>(cl, o, ws, p);
+        pa_merge_kernel<T, D, false><<<g, b, 0, stream>>>(cl, o, ws, p);
+}
+
+__global__ void workspace_init_kernel(int32_t *header) {
+    header[blockIdx.x * blockDim.x + threadIdx.x] = 0;
 }
 
 }  // namespace
 
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
-                        int dtype, int head_dim, bool base2, bool counted, int grid,
-                        hipStream_t stream) {
+                        int dtype, int head_dim, bool base2, int grid, hipStream_t stream) {
     if (dtype == KVC_F32) {
-        if (head_dim == 64) launch<float, 64>(base2, counted, context_lens, out, ws, p, grid, stream);
-        else launch<float, 128>(base2, counted, context_lens, out, ws, p, grid, stream);
+        if (head_dim == 64) launch<float, 64>(base2, context_lens, out, ws, p, grid, stream);
+        else launch<float, 128>(base2, context_lens, out, ws, p, grid, stream);
     } else {
-        if (head_dim == 64) launch<uint16_t, 64>(base2, counted, context_lens, out, ws, p, grid, stream);
-        else launch<uint16_t, 128>(base2, counted, context_lens, out, ws, p, grid, stream);
+        if (head_dim == 64) launch<uint16_t, 64>(base2, context_lens, out, ws, p, grid, stream);
+        else launch<uint16_t, 128>(base2, context_lens, out, ws, p, grid, stream);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_workspace_init(void *workspace, hipStream_t stream) {
+    constexpr int kWords = int(kWorkspaceHeaderBytes / sizeof(int32_t));
+    workspace_init_kernel<<<dim3(kWords / kThreads), dim3(kThreads), 0, stream>>>(static_cast<int32_t *>(workspace));
     return hipGetLastError();
 }
 

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kThreads, 3) void pa_partial_mfma_kernel(
     const int part = item / (p.num_kv_heads * p.num_seqs);
     const int G = p.group;
     const int head0 = kvh * G;
-    const int ctx = context_lens[seq];
+    const int ctx = min(context_lens[seq], p.max_context_len);
     const int tid = threadIdx.x;
 
     if (ctx <= 0) {  // empty context: zeros, written by partition 0

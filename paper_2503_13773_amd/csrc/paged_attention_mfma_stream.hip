@@ -1,4 +1,4 @@
-// Load-balanced persistent partial kernel of paged decode attention on the matrix cores
+// Load-balanced persistent kernel of paged decode attention on the matrix cores, one launch
 // (gfx950, bf16, head_dim 128, block_size >= 4, group <= 16, <= 4096 sequences).
 //
 // The serving traces this path sees have heavily skewed context lengths (a lognormal mix:
@@ -23,12 +23,31 @@
 // the same rate and all workers finish within a few percent of each other.
 //
 // A worker's range may start and end inside a row; each (row, tile range) it covers is a
-// "segment".  A segment that is a whole row is normalised and written to `out`; otherwise
-// the worker writes (max, sum, accumulator) to partial slot (worker - first worker of the
-// row), and the worker that owns tile 0 of a row records how many partials the row has.  The
-// merge kernel reads that count.  Wavefronts never synchronise with each other after the
-// start-up prefix sum, and every loop is bounded by the worker's static range, so every
-// wavefront exits.
+// "segment".  A segment that is a whole row is normalised and written to `out`.  Otherwise it
+// is a partial (max, sum, accumulator) of a cut row: the H partial when the segment does not
+// start at the row's tile 0 (only a worker's first segment can), the T partial when it starts
+// at tile 0 but stops before the row ends (only its last segment can).  A row cut over workers
+// j0 .. j0+cnt-1 therefore has its partials in T[j0], H[j0+1], ..., H[j0+cnt-1], and the
+// workspace needs two partial slots per worker whatever the batch looks like.
+//
+// Cut rows are finished inside this kernel, with no second launch.  Which rows a worker holds
+// a piece of follows from its placement alone.  Per cut row there is one counter word (indexed
+// by j0: a worker is the first of at most one cut row; arrivals in the lower half of the word,
+// publications in the upper half).  A worker
+//   1. announces its arrival (adds 1 to the word of each of its cut rows) right after it has
+//      issued the loads of its last tile, so the counter's answer travels while the last one or
+//      two tiles are consumed; the H partial was parked in registers meanwhile;
+//   2. where the add returned cnt-1 it is the last to arrive and finishes the row: it waits
+//      until the upper half shows the other cnt-1 pieces published (a poll, usually short),
+//      fetches them with device-scope loads, merges all cnt partials in slot order by the
+//      log-sum-exp rule (its own from registers: the same values its slot would hold, so the
+//      result does not depend on who arrived last), writes `out` and resets the word to 0;
+//   3. elsewhere it writes its partial to its slot with device-scope stores, waits for them to
+//      complete and adds 0x10000 (published).
+// The only wait on another wavefront is the poll in 2: the wavefronts polled for have already
+// arrived, which they do one or two tiles before the end of their range; what they have left
+// (those tiles, their stores, one add) needs nothing from anyone, so the poll ends.  The
+// counter words must be 0 when the kernel starts and are 0 again when it ends.
 //
 // The worker's tiles form one continuous stream, software-pipelined over two register sets:
 // the loads of tile i+1 are issued before tile i is consumed, also when tile i+1 belongs to
@@ -52,9 +71,191 @@ using namespace mfma;
 
 __device__ inline int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Partials cross from one wavefront to another inside a launch, between XCDs whose L2 caches
+// are not coherent with each other.  They are therefore written and read with device-scope
+// accesses (the sc1 cache policy: each access goes to the point of coherence of the whole
+// device by itself), 16 bytes per lane, through raw buffer instructions, instead of ordinary
+// stores followed by a write-back of the whole L2: that write-back, issued by 1024 wavefronts,
+// doubled the kernel time when it was measured.
+constexpr int kDeviceScope = 16;  // cache-policy operand of the buffer builtins: sc1
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ inline __amdgpu_buffer_rsrc_t raw_buffer(const void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+__device__ inline void store4_device_scope(__amdgpu_buffer_rsrc_t b, uint32_t byte_off, float x, float y, float z, float w) {
+    const u32x4 v = {__float_as_uint(x), __float_as_uint(y), __float_as_uint(z), __float_as_uint(w)};
+    __builtin_amdgcn_raw_buffer_store_b128(v, b, byte_off, 0, kDeviceScope);
+}
+__device__ inline float4 load4_device_scope(__amdgpu_buffer_rsrc_t b, uint32_t byte_off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(b, byte_off, 0, kDeviceScope);
+    return float4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+}
+__device__ inline void store2_device_scope(__amdgpu_buffer_rsrc_t b, uint32_t byte_off, float x, float y) {
+    const u32x2 v = {__float_as_uint(x), __float_as_uint(y)};
+    __builtin_amdgcn_raw_buffer_store_b64(v, b, byte_off, 0, kDeviceScope);
+}
+__device__ inline float2 load2_device_scope(__amdgpu_buffer_rsrc_t b, uint32_t byte_off) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(b, byte_off, 0, kDeviceScope);
+    return float2{__uint_as_float(v.x), __uint_as_float(v.y)};
+}
+
 constexpr int kStageTiles = 256;  // tiles whose addresses are staged in LDS per wavefront at a time
 constexpr int kMaxUnits = 4;      // a 16-token tile spans up to 4 blocks (block_size 4)
 constexpr int kRowCost = 1;       // flat units charged for leaving a row
+static_assert(size_t(kNumCUs) * kWaves * sizeof(int32_t) <= kWorkspaceHeaderBytes,
+              "one arrival counter per worker must fit the workspace header");
+
+// ---- finishing cut rows --------------------------------------------------------------------
+// A cut row as seen by the worker that arrived last at it.
+struct CutRow {
+    bool active;
+    int n, kvh;   // sequence, KV head
+    int j0, cnt;  // first worker of the row, number of workers on it
+    int own;      // which of the cnt partials is this worker's own
+};
+
+
+// Partial slot layout (fp32): [8 vectors][quad][head][4]; vector v of (quad, head) = dims
+// 32*quad + 4v .. +3 of the head's accumulator; (max, sum) per head in a second array.  One
+// store or load instruction of a wavefront then covers whole 128-byte lines.  Offsets in bytes.
+__device__ inline uint32_t slot_vec(int slot, int G, int v, int quad, int head) {
+    return (uint32_t(slot) * uint32_t(G * mfma::D) + uint32_t(((v * 4 + quad) * G + head) * 4)) * 4u;
+}
+__device__ inline uint32_t slot_ml(int slot, int G, int head) { return uint32_t(slot * G + head) * 8u; }
+__device__ inline int slot_of_partial(int j0, int i) { return i == 0 ? 2 * j0 + 1 : 2 * (j0 + i); }
+// vector v of a lane's accumulator registers: dims 4v .. 4v+3 of its 32-dim slice
+__device__ inline float4 acc_vec(const mfma::HeadState &x, int v) {
+    const int e = 4 * (v & 1), i = v >> 1;
+    return float4{x.acc[e][i], x.acc[e + 1][i], x.acc[e + 2][i], x.acc[e + 3][i]};
+}
+
+// Log-sum-exp merge of the partials of up to two cut rows, in slot order, and the write of the
+// rows.  The loads of both rows are issued before anything is consumed (device-scope loads
+// are slow, ~40 ns each per wavefront when measured, so only partials that exist and are not
+// the worker's own are fetched).  PV = 4-dim vectors per lane: with PV = 8 lane (quad, r)
+// merges all 32 dims of head r (lanes r >= G idle); with PV = 2 or 4 (G <= 2 PV) the 32 dims
+// are spread over the 8 / PV lanes (quad, head + 2 PV * sub), so all lanes work and a lane has
+// 8 / PV times fewer loads in flight.  The worker's own partial comes from its registers
+// (`mine`, re-distributed through `lds`, >= 128 * G floats private to the wavefront, when
+// PV < 8): the same values its slot holds, so the result does not depend on which worker merges.
+template <int PV>
+__device__ inline void merge_cut_rows(__amdgpu_buffer_rsrc_t acc_buf, __amdgpu_buffer_rsrc_t ml_buf,
+                                      uint16_t *out, int G, int num_q_heads, int lane, float *lds,
+                                      const CutRow (&row)[2], const mfma::HeadState &mine0,
+                                      const mfma::HeadState &mine1) {
+    using namespace mfma;
+    constexpr int HP = 2 * PV;  // heads a quad row of 16 lanes can carry: 4, 8 or 16
+    const int quad = lane >> 4, r = lane & 15;
+    const int head = PV == 8 ? r : (r & (HP - 1)), sub = PV == 8 ? 0 : r / HP;
+    const bool active = head < G;
+    const int hd = active ? head : 0;
+
+    float4 own_x[2][PV];
+    float2 own_ml[2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        const HeadState &mine = w == 0 ? mine0 : mine1;
+        if (!row[w].active) continue;
+        if constexpr (PV == 8) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) own_x[w][v] = acc_vec(mine, v);
+            own_ml[w] = float2{mine.m, mine.l};
+        } else {
+            if (r < G) {
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    *reinterpret_cast<float4 *>(lds + slot_vec(0, G, v, quad, r) / 4) = acc_vec(mine, v);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int vv = 0; vv < PV; ++vv)
+                own_x[w][vv] = *reinterpret_cast<const float4 *>(lds + slot_vec(0, G, PV * sub + vv, quad, hd) / 4);
+            own_ml[w] = float2{__shfl(mine.m, (lane & 48) | hd), __shfl(mine.l, (lane & 48) | hd)};
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+
+    constexpr int kMergeBatch = 16 / PV;  // partials of a row fetched together (64 registers per row)
+    float2 ml[2][kMergeBatch];
+    float4 x[2][kMergeBatch][PV];
+    auto issue = [&](int w, int c0) __attribute__((always_inline)) {
+        if (active) {
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) {
+                // wavefront-uniform: nothing is fetched past the row's partials, nor this worker's own
+                if (c0 + u >= row[w].cnt || c0 + u == row[w].own) continue;
+                const int slot = slot_of_partial(row[w].j0, c0 + u);
+                ml[w][u] = load2_device_scope(ml_buf, slot_ml(slot, G, hd));
+#pragma unroll
+                for (int vv = 0; vv < PV; ++vv)
+                    x[w][u][vv] = load4_device_scope(acc_buf, slot_vec(slot, G, PV * sub + vv, quad, hd));
+            }
+        }
+    };
+#pragma unroll
+    for (int w = 0; w < 2; ++w)
+        if (row[w].active) issue(w, 0);
+
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        if (!row[w].active) continue;
+        const int cnt = row[w].cnt;
+        float M = -INFINITY, L = 0.f;
+        float4 a[PV];
+#pragma unroll
+        for (int vv = 0; vv < PV; ++vv) a[vv] = float4{0.f, 0.f, 0.f, 0.f};
+        for (int c0 = 0; c0 < cnt; c0 += kMergeBatch) {
+            if (c0 > 0) issue(w, c0);
+            float mc = M;
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) {
+                if (c0 + u == row[w].own) {  // wavefront-uniform
+                    ml[w][u] = own_ml[w];
+#pragma unroll
+                    for (int vv = 0; vv < PV; ++vv) x[w][u][vv] = own_x[w][vv];
+                }
+                if (c0 + u >= cnt) {         // past the row's partials: weight 0 below
+                    ml[w][u] = float2{-INFINITY, 0.f};
+#pragma unroll
+                    for (int vv = 0; vv < PV; ++vv) x[w][u][vv] = float4{0.f, 0.f, 0.f, 0.f};
+                }
+                mc = fmaxf(mc, ml[w][u].x);  // finite: every partial holds at least one token
+            }
+            const float alpha = __builtin_amdgcn_exp2f(M - mc);
+            M = mc;
+            L *= alpha;
+#pragma unroll
+            for (int vv = 0; vv < PV; ++vv) { a[vv].x *= alpha; a[vv].y *= alpha; a[vv].z *= alpha; a[vv].w *= alpha; }
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) {
+                const float wgt = c0 + u < cnt ? __builtin_amdgcn_exp2f(ml[w][u].x - M) : 0.f;
+                L = fmaf(wgt, ml[w][u].y, L);
+#pragma unroll
+                for (int vv = 0; vv < PV; ++vv) {
+                    a[vv].x = fmaf(wgt, x[w][u][vv].x, a[vv].x);
+                    a[vv].y = fmaf(wgt, x[w][u][vv].y, a[vv].y);
+                    a[vv].z = fmaf(wgt, x[w][u][vv].z, a[vv].z);
+                    a[vv].w = fmaf(wgt, x[w][u][vv].w, a[vv].w);
+                }
+            }
+        }
+        if (active) {
+            const float inv = 1.0f / L;
+            uint16_t *dst = out + (size_t(row[w].n) * num_q_heads + row[w].kvh * G + head) * D + 32 * quad + 4 * PV * sub;
+#pragma unroll
+            for (int v = 0; v < PV / 2; ++v) {
+                uint4 o;
+                o.x = pack_bf16(a[2 * v].x * inv, a[2 * v].y * inv);
+                o.y = pack_bf16(a[2 * v].z * inv, a[2 * v].w * inv);
+                o.z = pack_bf16(a[2 * v + 1].x * inv, a[2 * v + 1].y * inv);
+                o.w = pack_bf16(a[2 * v + 1].z * inv, a[2 * v + 1].w * inv);
+                *reinterpret_cast<uint4 *>(dst + 8 * v) = o;
+            }
+        }
+    }
+}
 
 // A row of the flattened work: (sequence, KV head); all fields wavefront-uniform.
 struct RowCursor {
@@ -93,7 +294,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             const int n = tid * spt + i;
             int t = 0;
             if (i < spt && n < nseq) {
-                const int c = max(context_lens[n], 0);
+                const int c = min(max(context_lens[n], 0), p.max_context_len);
                 s_ctx[n] = c;
                 t = (c + kTileTokens - 1) >> 4;
                 if (t > 0) t += kRowCost;
@@ -122,6 +323,14 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             s_pref[nseq + 1] = excl + sum + 1 + kRowCost;  // guard: "sequence nseq" looks non-empty, stops row walks
         }
         __syncthreads();
+    }
+
+    // empty contexts give rows of zeros; workgroup b looks after sequences b, b + grid, ...
+    for (int n = blockIdx.x; n < nseq; n += gridDim.x) {
+        if (s_ctx[n] == 0) {
+            uint4 *row = reinterpret_cast<uint4 *>(out + size_t(n) * p.num_q_heads * D);
+            for (int i = tid; i < p.num_q_heads * (D / 8); i += kThreads) row[i] = uint4{0u, 0u, 0u, 0u};
+        }
     }
 
     const int Hkv = p.num_kv_heads;
@@ -174,15 +383,20 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             first_tile = 0;
         }
     }
-    // tiles of this worker: the part of [f0, f1) that falls on tiles rather than cost units
+    // tiles of this worker: the part of [f0, f1) that falls on tiles rather than cost units;
+    // the walk also finds the last row it touches and where its piece of that row ends
     int NT = 0;
+    RowCursor last = first;
+    int last_t0 = first_tile, last_end = first_tile;
     {
         RowCursor c = first;
         int t0 = first_tile;
         while (c.n < nseq) {
             const int row0 = c.pref * Hkv + c.kvh * (c.tiles + kRowCost);  // flat unit of the row's tile 0
             if (row0 + t0 >= f1) break;
-            NT += min(row0 + c.tiles, f1) - (row0 + t0);
+            const int e = min(row0 + c.tiles, f1) - row0;
+            NT += e - t0;
+            last = c; last_t0 = t0; last_end = e;
             if (row0 + c.tiles + kRowCost >= f1) break;
             c = next_row(c);
             t0 = 0;
@@ -261,16 +475,36 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     HeadState st;
     st.reset();
 
-    // Write the finished segment [seg_first, tc) of row rc.
+    // Cut rows this worker holds a piece of (at most one through slot H: its first segment, when
+    // that starts past the row's tile 0; at most one through slot T: its last segment, when that
+    // starts at tile 0 and stops before the row's end): sequence, KV head, first worker of the
+    // row, number of workers on the row (0 = none).  Known from the worker's placement alone, so
+    // that it can announce its arrival before its last tiles are consumed.  The H partial is
+    // parked in `hp` until the worker's end; the T partial is still in `st` then.
+    int h_n = 0, h_kvh = 0, h_j0 = 0, h_cnt = 0;
+    int t_n = 0, t_kvh = 0, t_j0 = 0, t_cnt = 0;
+    if (first_tile > 0) {
+        const int row_f = first.pref * Hkv + first.kvh * (first.tiles + kRowCost);
+        h_n = first.n; h_kvh = first.kvh; h_j0 = row_f / C;
+        h_cnt = (row_f + first.tiles - 1) / C - h_j0 + 1;
+    }
+    if (last_t0 == 0 && last_end < last.tiles) {
+        const int row_f = last.pref * Hkv + last.kvh * (last.tiles + kRowCost);
+        t_n = last.n; t_kvh = last.kvh; t_j0 = row_f / C;
+        t_cnt = (row_f + last.tiles - 1) / C - t_j0 + 1;
+    }
+    HeadState hp;
+    hp.reset();
+
+    // The segment [seg_first, tc) of row rc is finished: a whole row goes to `out`, a piece of a
+    // cut row is kept for the publication at the end of the worker.
     auto finalize = [&]() __attribute__((always_inline)) {
         st.finish();
-        const int row_f = rc.pref * Hkv + rc.kvh * (rc.tiles + kRowCost);  // flat unit of the row's tile 0
-        const int j0 = row_f / C;
-        const int cnt = (row_f + rc.tiles - 1) / C - j0 + 1;  // workers that touch this row
-        const int slot = worker - j0;                         // my partial index within the row
-        if (r < G) {  // lane (quad, r) holds O[head r][32*quad .. +31]
-            const size_t orow = size_t(rc.n) * p.num_q_heads + rc.kvh * G + r;
-            if (cnt == 1) {
+        if (seg_first > 0) {            // H piece
+            hp = st;
+        } else if (tc == rc.tiles) {    // whole row
+            if (r < G) {  // lane (quad, r) holds O[head r][32*quad .. +31]
+                const size_t orow = size_t(rc.n) * p.num_q_heads + rc.kvh * G + r;
                 const float inv = 1.0f / st.l;
                 uint16_t *dst = out + orow * D + 32 * quad;
 #pragma unroll
@@ -282,18 +516,45 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
                     w.w = pack_bf16(st.acc[6][i] * inv, st.acc[7][i] * inv);
                     *reinterpret_cast<uint4 *>(dst + 8 * i) = w;
                 }
-            } else if (slot < p.max_partitions) {
-                const size_t ps = orow * p.max_partitions + slot;
-                float *dst = ws.acc + ps * D + 32 * quad;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    *reinterpret_cast<float4 *>(dst + 8 * i) = float4{st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]};
-                    *reinterpret_cast<float4 *>(dst + 8 * i + 4) = float4{st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]};
-                }
-                if (quad == 0) *reinterpret_cast<float2 *>(ws.ml + ps * 2) = float2{st.m, st.l};
             }
+        }                               // else: T piece, stays in `st`
+    };
+
+    // Arrival at the cut rows: 1 is added to the lower half of their counter words.
+    int oh = 0, ot = 0;
+    auto arrive = [&]() __attribute__((always_inline)) {
+        if (lane == 0) {
+            if (h_cnt) oh = __hip_atomic_fetch_add(ws.cnt + h_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t_cnt) ot = __hip_atomic_fetch_add(ws.cnt + t_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (seg_first == 0 && lane == 0) ws.cnt[rc.n * Hkv + rc.kvh] = cnt;
+    };
+
+    const uint32_t slots = 2u * gridDim.x * kWaves;
+    const __amdgpu_buffer_rsrc_t acc_buf = raw_buffer(ws.acc, slots * uint32_t(G * D) * 4u);
+    const __amdgpu_buffer_rsrc_t ml_buf = raw_buffer(ws.ml, slots * uint32_t(G) * 8u);
+    auto store_partial = [&](int slot, const HeadState &x) __attribute__((always_inline)) {
+        if (r < G) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const float4 f = acc_vec(x, v);
+                store4_device_scope(acc_buf, slot_vec(slot, G, v, quad, r), f.x, f.y, f.z, f.w);
+            }
+            if (quad == 0) store2_device_scope(ml_buf, slot_ml(slot, G, r), x.m, x.l);
+        }
+    };
+
+    // The last worker to arrive at a cut row finishes it.  `seen` is the counter word its
+    // arrival returned: when some earlier arrival has not published yet (upper half below
+    // cnt - 1) it polls.  The workers polled for have already arrived: they have at most two
+    // tiles to consume, their stores to wait for and one add to make, none of which depends on
+    // another wavefront, so the poll ends; the cap only keeps a wavefront from spinning forever
+    // should that reasoning ever be wrong.
+    auto await_publications = [&](int j0, int cnt, int seen) __attribute__((always_inline)) {
+        int spins = 0;
+        while ((seen >> 16) != cnt - 1 && ++spins < (1 << 22)) {
+            __builtin_amdgcn_s_sleep(2);
+            seen = uniform(__hip_atomic_load(ws.cnt + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
     };
 
     // Consumes the tile under the compute cursor.  When it was the last tile of the row the
@@ -320,24 +581,72 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
 
     // Two register sets; the steady-state loop has no branch around the tile loads, so the
     // compiler's wait counts let the newest 8 loads stay in flight while the older tile is
-    // consumed.  The 1- or 2-tile tail is peeled.
+    // consumed.  The last 1 to 3 tiles are peeled; the worker announces its arrival at its cut
+    // rows right after the loads of its last tile have been issued, so that the counter's
+    // answer travels while the last tiles are consumed.
     uint4 kA[4], vA[4], kB[4], vB[4];
     issue_next(kA, vA);
     int it = 0;
-    for (; it + 2 < NT; it += 2) {
+    for (; it + 3 < NT; it += 2) {
         issue_next(kB, vB);
         compute_next(kA, vA, true);
         issue_next(kA, vA);
         compute_next(kB, vB, true);
     }
-    if (it + 1 < NT) {
+    if (it + 3 == NT) {
         issue_next(kB, vB);
+        compute_next(kA, vA, true);
+        issue_next(kA, vA);
+        arrive();
+        compute_next(kB, vB, true);
+        compute_next(kA, vA, false);
+    } else if (it + 2 == NT) {
+        issue_next(kB, vB);
+        arrive();
         compute_next(kA, vA, true);
         compute_next(kB, vB, false);
     } else {
+        arrive();
         compute_next(kA, vA, false);
     }
     finalize();
+
+    // ---- cut rows: publish, and finish the rows this worker was the last to arrive at.
+    // Counter word of a row (indexed by its first worker): arrivals in the lower half,
+    // publications in the upper half.  If the worker's arrival was the last it merges, taking
+    // its own piece from registers and polling for pieces that arrived but are not published
+    // yet.  Otherwise it waits until its partial stores (device-scope accesses) have completed
+    // and adds 0x10000; the workgroup-scope release is that wait, and keeps the compiler from
+    // moving the stores.
+    if (h_cnt | t_cnt) {
+        oh = uniform(oh);
+        ot = uniform(ot);
+        const bool last_h = h_cnt && (oh & 0xffff) == h_cnt - 1, last_t = t_cnt && (ot & 0xffff) == t_cnt - 1;
+        if ((h_cnt && !last_h) || (t_cnt && !last_t)) {
+            if (h_cnt && !last_h) store_partial(2 * worker, hp);
+            if (t_cnt && !last_t) store_partial(2 * worker + 1, st);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) {
+                if (h_cnt && !last_h) __hip_atomic_fetch_add(ws.cnt + h_j0, 0x10000, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (t_cnt && !last_t) __hip_atomic_fetch_add(ws.cnt + t_j0, 0x10000, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (last_t | last_h) {
+            const CutRow rows[2] = {{last_t, t_n, t_kvh, t_j0, t_cnt, 0}, {last_h, h_n, h_kvh, h_j0, h_cnt, worker - h_j0}};
+            if (last_t) await_publications(t_j0, t_cnt, ot);
+            if (last_h) await_publications(h_j0, h_cnt, oh);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            float *lds = reinterpret_cast<float *>(&s_tile[wave][0]);  // the tile addresses are no longer needed
+            if (G <= 4) merge_cut_rows<2>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
+            else if (G <= 8) merge_cut_rows<4>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
+            else merge_cut_rows<8>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
+            // every arrival and publication of these rows has happened: leave their counters at 0
+            if (lane == 0) {
+                if (last_t) __hip_atomic_store(ws.cnt + t_j0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (last_h) __hip_atomic_store(ws.cnt + h_j0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
 }
 
 }  // namespace

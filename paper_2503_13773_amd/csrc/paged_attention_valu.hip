@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void pa_partial_valu_kernel(
         if (Qn > S || i >= max_query_len) return;
         ctx = S - Qn + i + 1;
     } else {
-        ctx = context_lens[seq];
+        ctx = min(context_lens[seq], p.max_context_len);
     }
 
     if (ctx <= 0) {  // empty context: a row of zeros, written by partition 0

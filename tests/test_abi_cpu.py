@@ -88,8 +88,12 @@ def plan_status(K, d):
 
 def test_plan_picks_kernels_and_sizes_workspace(K):
     rc, p = plan_status(K, desc(K))
-    assert rc == 0 and p.kernel == K.KERNEL_MFMA_BALANCED and p.partial_grid == 256 and p.merge_grid == 512
-    assert p.max_partitions == 33 and p.workspace_bytes == K.workspace_bytes(desc(K)) > 0
+    assert rc == 0 and p.kernel == K.KERNEL_MFMA_BALANCED and p.partial_grid == 256 and p.merge_grid == 0
+    # balanced kernel: two partial slots per wavefront, sized by the group only
+    slots = 256 * 4 * 2
+    assert p.max_partitions == 2 and p.workspace_bytes == K.workspace_bytes(desc(K)) == \
+        4096 + slots * 4 * 128 * 4 + slots * 4 * 2 * 4
+    assert K.workspace_bytes(desc(K, num_seqs=3, max_context_len=64)) == p.workspace_bytes
     rc, p = plan_status(K, desc(K, dtype=K.KVC_F32, head_dim=64, num_q_heads=8, num_kv_heads=8,
                                 max_blocks_per_seq=16))
     assert rc == 0 and p.kernel == K.KERNEL_VALU and p.max_partitions == 1 and p.workspace_bytes == 0

@@ -38,7 +38,7 @@ def test_decode_iteration_graph_replays_match_eager_and_oracle(oracle_mod):
     v_new = torch.zeros_like(k_new)
     out = torch.empty_like(q)
     desc = K.attn_desc(q, kc, tables, max_context_len=int(lens0.max()) + 3)
-    ws = torch.empty(max(1, K.workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+    ws = K.new_workspace(desc)      # counter header zeroed once; every call leaves it zeroed, replays too
     # swap-out of the first two sequences' blocks into a second pool
     victims = [b for n in (0, 1) for b in w.block_tables[n, :int(nblk[n])]]
     pool2 = torch.zeros((2, len(victims)) + tuple(kc.shape[1:]), dtype=kc.dtype, device="cuda")

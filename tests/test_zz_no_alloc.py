@@ -41,7 +41,7 @@ def test_noalloc_refuses_what_does_not_fit_and_bad_arguments():
     out = torch.empty_like(d["q"])
     big = K.AttnDesc(num_seqs=4096, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16,
                      max_blocks_per_seq=256, num_pool_blocks=1 << 20, dtype=K.KVC_BF16,
-                     max_context_len=4096, partition_tokens=0, kernel=0, reserved=0)
+                     max_context_len=4096, partition_tokens=256, kernel=K.KERNEL_MFMA, reserved=0)
     assert K.workspace_bytes(big) > K.NOALLOC_WORKSPACE_BYTES
     rc = K.lib().kvc_paged_attention_decode_noalloc(d["q"].data_ptr(), d["k"].data_ptr(), d["v"].data_ptr(),
                                                     d["tables"].data_ptr(), d["lens"].data_ptr(), w.scale,
