@@ -95,6 +95,120 @@ KVCP_API double kvcp_sweet_spot(double gamma_s, double delta_s, double alpha_r, 
 /* 1 = swap, 0 = recompute: swap iff the sequence length exceeds the sweet spot. */
 KVCP_API int kvcp_choose_swap(double seq_len, double sweet_spot);
 
+/* Least-squares fits of the two profiled latency curves (Section 3.5).  n >= 2 points with
+ * distinct x; r2 (coefficient of determination in the fitted space) may be NULL.  Return 0, or
+ * -1 on bad arguments (n < 2, non-finite values, all x equal; the power law also needs x > 0
+ * and y > 0).
+ *   kvcp_fit_linear:     y = gamma * x + delta                 (swapping: L_s = gamma_s S + delta_s)
+ *   kvcp_fit_power_law:  y = alpha * x^beta, fitted as a line in (ln x, ln y)
+ *                        (recomputation with kappa_r = eps_r = 0) */
+KVCP_API int kvcp_fit_linear(const double *x, const double *y, int64_t n, double *gamma, double *delta,
+                             double *r2);
+KVCP_API int kvcp_fit_power_law(const double *x, const double *y, int64_t n, double *alpha, double *beta,
+                                double *r2);
+
+/* ---- one scheduler step: batch formation and KVC allocation (Section 3.3.2, 3.3.3, 3.4, 3.5) ---- */
+
+enum { KVCP_WAITING = 0, /* in the queue: new, or preempted earlier and waiting to come back */
+       KVCP_RUNNING = 1  /* was in the batch of the iteration that just returned ("returned request") */ };
+enum { KVCP_KEEP = 0, KVCP_PREEMPT_SWAP = 1, KVCP_PREEMPT_RECOMPUTE = 2 };
+enum { KVCP_CASE_EQUAL = 0, KVCP_CASE_LESS = 1, KVCP_CASE_MORE = 2 };
+
+typedef struct {
+    int32_t state;           /* KVCP_WAITING or KVCP_RUNNING */
+    int32_t reserved;        /* must be 0 */
+    int64_t prompt_len;      /* s^p_i > 0 */
+    int64_t est_output_len;  /* s^o_i >= 1, after padding (Section 3.2) */
+    int64_t generated;       /* output tokens produced so far */
+    int64_t allocated;       /* a_i: KVC tokens allocated to it (0 while waiting) */
+    int64_t used;            /* u_i: KVC tokens it occupies (0 while waiting) */
+    double remaining_time;   /* RT_i > 0: time left to its TTFT SLO (waiting and never ran) or to its
+                                TBT SLO (otherwise) */
+    double tbt_slo;          /* its TBT SLO (preemption order) */
+} kvcp_request;
+
+typedef struct {
+    int64_t unallocated;     /* A'_kvc: KVC tokens allocated to nobody */
+    int64_t block_tokens;    /* B: allocation granule in tokens */
+    int64_t buffer_tokens;   /* b of the embedding method */
+    int64_t token_budget;    /* tokens one iteration should process: a running request counts 1,
+                                a waiting one its prompt */
+    int64_t token_bucket;    /* bucket width of the preemption order (tokens) */
+    int32_t m;               /* proactive allocation: horizon in iterations */
+    int32_t n_slo_edges;
+    const double *slo_edges; /* TBT-SLO bucket edges of the preemption order (host, ascending) */
+    double max_iteration_latency;  /* T_I^max */
+    double eps;
+    double iter_time_base;       /* iteration latency model base + per_token * tokens, used when */
+    double iter_time_per_token;  /* requests are added in the case sum M < A'_kvc */
+    double sweet_spot;           /* S_s: sequences longer than this are swapped, others recomputed */
+} kvcp_step_params;
+
+typedef struct {
+    int32_t in_batch;   /* 1: runs in the next iteration */
+    int32_t critical;   /* 1: member of N_w or N_r */
+    int32_t preempt;    /* KVCP_KEEP, KVCP_PREEMPT_SWAP or KVCP_PREEMPT_RECOMPUTE */
+    int32_t proactive;  /* 1: joined the allocation round through the m-iteration rule */
+    int64_t grant;      /* KVC tokens newly allocated to it out of the unallocated KVC */
+    int64_t host;       /* index of the running request it is embedded in, else -1 */
+    int64_t s0;         /* start offset inside the host's allocation in tokens (host >= 0 only) */
+    int64_t lender;     /* index of the running request whose released KVC it will use for its
+                           shortfall, else -1 */
+    int64_t shortfall;  /* part of its total demand M_i covered neither by its allocation, its grant
+                           nor an embedding */
+} kvcp_decision;
+
+typedef struct {
+    int64_t unallocated_after;  /* A'_kvc left when the step is done */
+    int64_t basic_demand;       /* D_kvc of the critical requests that were not embedded */
+    int64_t excess;             /* E_kvc = sum M - A'_kvc when the demands were amortised, else 0 */
+    int64_t batch_tokens;       /* tokens the formed batch processes */
+    int32_t n_preempted;
+    int32_t alloc_case;         /* KVCP_CASE_* of the allocation of the remaining KVC */
+} kvcp_step_summary;
+
+/*
+ * Forms the next batch and allocates KVC, in the order of Section 3.3.2:
+ *   1. Running requests with unused allocation stay in the batch.  A running request that has
+ *      used up its allocation is critical (N_r) when RT - T_I^max < eps, else it is in N'_r;
+ *      waiting requests with RT - T_I^max < eps are critical (N_w).
+ *   2. Critical requests, in descending order of their basic requirement (s^p_i + B waiting, B
+ *      returned): a waiting one is first tried with the embedding method (host = running request
+ *      with unused allocation and the least of it that fits; a host takes one guest per step);
+ *      the others need D_kvc of unallocated KVC.  While A'_kvc < D_kvc, running requests that are
+ *      neither critical nor hosts are preempted in the order of Section 3.4, each by swapping if
+ *      its occupied KVC exceeds the sweet spot and by recomputation otherwise (Section 3.5); a
+ *      victim's allocation returns to A'_kvc.  Then every critical request is granted its basic
+ *      requirement (in that order, as long as it fits).
+ *   3. The allocation round for the remaining KVC is joined by the critical requests, N'_r,
+ *      unfulfilled running requests (a_i < M_i) predicted to finish within m iterations
+ *      (Section 3.3.3), and N'_w: waiting requests in ascending RT taken while the batch stays
+ *      within the token budget.  Waiting ones are tried with the embedding method first (demand
+ *      0 when embedded).  Demands are what is missing to M_i = s^p_i + s^o_i (a request already
+ *      beyond its estimate asks for B).  Three cases:
+ *        sum = A'_kvc  everybody gets its demand;
+ *        sum < A'_kvc  further waiting requests are added in ascending RT while their whole M_i still
+ *                      fits and the modelled iteration time stays below every batched request's RT;
+ *        sum > A'_kvc  the printed amortisation (kvcp_allocate).
+ *      A new request whose share cannot hold its prompt plus B is left out and the round is
+ *      repeated without it; alloc_case and excess describe the last round.
+ *   4. A batched request with a shortfall borrows: lender = running request in the batch that
+ *      finishes (s^o_j - generated_j iterations) no later than the borrower exhausts what it
+ *      holds, holds at least the shortfall, and among those finishes latest (then holds least);
+ *      a request lends once.
+ * req[0..n) and out[0..n) are host arrays; summary may be NULL.  Returns 0, or -1 on invalid
+ * arguments (nothing is written then).
+ */
+KVCP_API int kvcp_schedule_step(const kvcp_request *req, int64_t n, const kvcp_step_params *params,
+                                kvcp_decision *out, kvcp_step_summary *summary);
+
+/* Blocks of the host's block list an embedded request occupies: it starts at the first block
+ * boundary at or after token offset s0 and spans ceil((sp_i + so_i) / block_size) blocks, so guest
+ * and host never share a block.  Returns 0 and stores first / count, or -1 when rounding to
+ * blocks pushes it past the host's host_blocks blocks. */
+KVCP_API int kvcp_embedding_block_range(int64_t s0, int64_t sp_i, int64_t so_i, int64_t block_size,
+                                        int64_t host_blocks, int64_t *first, int64_t *count);
+
 /* ---- block manager with a globally reserved pool (Section 3.3.3) ---- */
 
 typedef struct kvcp_block_manager kvcp_block_manager;

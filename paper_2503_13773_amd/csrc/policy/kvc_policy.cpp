@@ -146,6 +146,317 @@ double kvcp_sweet_spot(double gamma_s, double delta_s, double alpha_r, double be
 
 int kvcp_choose_swap(double seq_len, double sweet_spot) { return seq_len > sweet_spot ? 1 : 0; }
 
+// Ordinary least squares of y on x; also the coefficient of determination.
+static int fit_line(const std::vector<double> &x, const std::vector<double> &y, double *slope,
+                    double *intercept, double *r2) {
+    const size_t n = x.size();
+    double mx = 0.0, my = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        if (!std::isfinite(x[i]) || !std::isfinite(y[i])) return -1;
+        mx += x[i];
+        my += y[i];
+    }
+    mx /= double(n);
+    my /= double(n);
+    double sxx = 0.0, sxy = 0.0, syy = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        sxx += (x[i] - mx) * (x[i] - mx);
+        sxy += (x[i] - mx) * (y[i] - my);
+        syy += (y[i] - my) * (y[i] - my);
+    }
+    if (!(sxx > 0.0)) return -1;
+    const double k = sxy / sxx, c = my - k * mx;
+    if (slope) *slope = k;
+    if (intercept) *intercept = c;
+    if (r2) {
+        double sse = 0.0;
+        for (size_t i = 0; i < n; ++i) {
+            const double e = y[i] - (k * x[i] + c);
+            sse += e * e;
+        }
+        *r2 = syy > 0.0 ? 1.0 - sse / syy : 1.0;
+    }
+    return 0;
+}
+
+int kvcp_fit_linear(const double *x, const double *y, int64_t n, double *gamma, double *delta, double *r2) {
+    if (n < 2 || !x || !y || !gamma || !delta) return -1;
+    return fit_line(std::vector<double>(x, x + n), std::vector<double>(y, y + n), gamma, delta, r2);
+}
+
+int kvcp_fit_power_law(const double *x, const double *y, int64_t n, double *alpha, double *beta, double *r2) {
+    if (n < 2 || !x || !y || !alpha || !beta) return -1;
+    std::vector<double> lx(n), ly(n);
+    for (int64_t i = 0; i < n; ++i) {
+        if (!(x[i] > 0.0) || !(y[i] > 0.0)) return -1;
+        lx[i] = std::log(x[i]);
+        ly[i] = std::log(y[i]);
+    }
+    double k, c;
+    if (fit_line(lx, ly, &k, &c, r2) != 0) return -1;
+    *beta = k;
+    *alpha = std::exp(c);
+    return 0;
+}
+
+int kvcp_embedding_block_range(int64_t s0, int64_t sp_i, int64_t so_i, int64_t block_size,
+                               int64_t host_blocks, int64_t *first, int64_t *count) {
+    if (s0 < 0 || sp_i < 0 || so_i < 0 || block_size <= 0 || host_blocks < 0 || !first || !count) return -1;
+    const int64_t f = (s0 + block_size - 1) / block_size;
+    const int64_t c = (sp_i + so_i + block_size - 1) / block_size;
+    if (f + c > host_blocks) return -1;
+    *first = f;
+    *count = c;
+    return 0;
+}
+
+int kvcp_schedule_step(const kvcp_request *req, int64_t n, const kvcp_step_params *p, kvcp_decision *out,
+                       kvcp_step_summary *summary) {
+    if (n < 0 || !p || (n > 0 && (!req || !out))) return -1;
+    if (p->unallocated < 0 || p->block_tokens <= 0 || p->buffer_tokens < 0 || p->token_budget < 0 ||
+        p->token_bucket <= 0 || p->m < 0 || p->n_slo_edges < 0 || (p->n_slo_edges > 0 && !p->slo_edges) ||
+        !(p->iter_time_base >= 0.0) || !(p->iter_time_per_token >= 0.0) || std::isnan(p->sweet_spot) ||
+        std::isnan(p->max_iteration_latency) || std::isnan(p->eps))
+        return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        const kvcp_request &r = req[i];
+        if ((r.state != KVCP_WAITING && r.state != KVCP_RUNNING) || r.reserved != 0 || r.prompt_len <= 0 ||
+            r.est_output_len < 1 || r.generated < 0 || r.allocated < 0 || r.used < 0 || r.used > r.allocated ||
+            !(r.remaining_time > 0.0) || std::isnan(r.tbt_slo))
+            return -1;
+        if (r.state == KVCP_WAITING && (r.allocated != 0 || r.used != 0)) return -1;
+    }
+    const int64_t B = p->block_tokens;
+    int64_t avail = p->unallocated;
+    std::vector<kvcp_decision> d(n);
+    for (auto &x : d) x = kvcp_decision{0, 0, KVCP_KEEP, 0, 0, -1, 0, -1, 0};
+    auto total_demand = [&](int64_t i) { return req[i].prompt_len + req[i].est_output_len; };
+    auto critical_time = [&](int64_t i) {
+        return kvcp_is_critical(req[i].remaining_time, p->max_iteration_latency, p->eps) != 0;
+    };
+
+    // ---- 1. who is where
+    std::vector<int64_t> crit, nr_prime, waiting_rest;
+    std::vector<char> is_host(n, 0), out_of_kvc(n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+        if (req[i].state == KVCP_RUNNING) {
+            d[i].in_batch = 1;
+            if (req[i].used >= req[i].allocated) {
+                out_of_kvc[i] = 1;
+                if (critical_time(i)) { d[i].critical = 1; crit.push_back(i); }
+                else nr_prime.push_back(i);
+            }
+        } else if (critical_time(i)) {
+            d[i].critical = 1;
+            crit.push_back(i);
+        } else {
+            waiting_rest.push_back(i);
+        }
+    }
+    auto basic = [&](int64_t i) { return req[i].state == KVCP_WAITING ? req[i].prompt_len + B : B; };
+    std::stable_sort(crit.begin(), crit.end(), [&](int64_t x, int64_t y) { return basic(x) > basic(y); });
+    std::stable_sort(waiting_rest.begin(), waiting_rest.end(),
+                     [&](int64_t x, int64_t y) { return req[x].remaining_time < req[y].remaining_time; });
+
+    // Embedding method for waiting request i: host = running request with unused allocation, not out
+    // of KVC, not preempted, not a host already, with the least remaining allocation that fits.
+    auto try_embed = [&](int64_t i) {
+        int64_t best = -1, best_rem = 0, best_s0 = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (req[j].state != KVCP_RUNNING || out_of_kvc[j] || is_host[j] || d[j].preempt != KVCP_KEEP) continue;
+            int64_t s0;
+            if (!kvcp_embedding_fits(req[j].allocated, req[j].used, req[i].prompt_len, req[i].est_output_len,
+                                     p->buffer_tokens, &s0))
+                continue;
+            const int64_t rem = req[j].allocated - req[j].used;
+            if (best < 0 || rem < best_rem) { best = j; best_rem = rem; best_s0 = s0; }
+        }
+        if (best < 0) return false;
+        is_host[best] = 1;
+        d[i].host = best;
+        d[i].s0 = best_s0;
+        d[i].in_batch = 1;
+        return true;
+    };
+
+    // ---- 2. critical requests: embedding, preemptions up to the basic demand, basic grants
+    std::vector<int64_t> crit_unembedded;
+    int64_t D = 0;
+    for (int64_t i : crit) {
+        if (req[i].state == KVCP_WAITING && try_embed(i)) continue;
+        crit_unembedded.push_back(i);
+        D += basic(i);
+    }
+    int32_t n_preempted = 0;
+    if (avail < D) {
+        std::vector<int64_t> cand;
+        for (int64_t j = 0; j < n; ++j)
+            if (req[j].state == KVCP_RUNNING && !d[j].critical && !is_host[j]) cand.push_back(j);
+        std::vector<double> slo(cand.size());
+        std::vector<int64_t> rem(cand.size()), occ(cand.size()), order(cand.size());
+        for (size_t k = 0; k < cand.size(); ++k) {
+            slo[k] = req[cand[k]].tbt_slo;
+            rem[k] = std::max<int64_t>(0, req[cand[k]].est_output_len - req[cand[k]].generated);
+            occ[k] = req[cand[k]].used;
+        }
+        if (!cand.empty() &&
+            kvcp_preemption_order(slo.data(), rem.data(), occ.data(), int64_t(cand.size()), p->slo_edges,
+                                  p->n_slo_edges, p->token_bucket, order.data()) != 0)
+            return -1;
+        for (size_t k = 0; k < cand.size() && avail < D; ++k) {
+            const int64_t v = cand[order[k]];
+            d[v].preempt = kvcp_choose_swap(double(req[v].used), p->sweet_spot) ? KVCP_PREEMPT_SWAP
+                                                                               : KVCP_PREEMPT_RECOMPUTE;
+            d[v].in_batch = 0;
+            avail += req[v].allocated;
+            ++n_preempted;
+        }
+    }
+    for (int64_t i : crit_unembedded) {
+        if (basic(i) <= avail) {
+            d[i].grant = basic(i);
+            d[i].in_batch = 1;
+            avail -= basic(i);
+        } else {
+            d[i].in_batch = 0;  // not even the victims' KVC covers it: it waits
+        }
+    }
+
+    // ---- 3. the allocation round for the remaining KVC
+    int64_t batch_tokens = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if (d[i].in_batch) batch_tokens += req[i].state == KVCP_RUNNING ? 1 : req[i].prompt_len;
+    std::vector<int64_t> round;  // members with a demand (possibly 0)
+    std::vector<int64_t> demand(n, 0);
+    for (int64_t i : crit) {
+        if (!d[i].in_batch) continue;
+        if (d[i].host >= 0) continue;  // embedded: whole demand placed in the host
+        demand[i] = std::max<int64_t>(0, total_demand(i) - req[i].allocated - d[i].grant);
+        round.push_back(i);
+    }
+    for (int64_t i : nr_prime) {
+        if (d[i].preempt != KVCP_KEEP) continue;
+        const int64_t missing = total_demand(i) - req[i].allocated;
+        demand[i] = missing > 0 ? missing : B;
+        round.push_back(i);
+    }
+    for (int64_t i = 0; i < n; ++i) {  // proactive allocation: unfulfilled, about to finish
+        if (req[i].state != KVCP_RUNNING || out_of_kvc[i] || d[i].preempt != KVCP_KEEP) continue;
+        const int64_t left = req[i].est_output_len - req[i].generated;
+        if (req[i].allocated < total_demand(i) && left >= 0 && left <= p->m) {
+            d[i].proactive = 1;
+            demand[i] = total_demand(i) - req[i].allocated;
+            round.push_back(i);
+        }
+    }
+    size_t next_waiting = 0;
+    auto add_waiting = [&](int64_t i) {
+        d[i].in_batch = 1;
+        batch_tokens += req[i].prompt_len;
+        if (!try_embed(i)) demand[i] = total_demand(i);
+        round.push_back(i);
+    };
+    for (; next_waiting < waiting_rest.size(); ++next_waiting) {  // N'_w: up to the token budget
+        const int64_t i = waiting_rest[next_waiting];
+        if (batch_tokens + req[i].prompt_len > p->token_budget) break;
+        add_waiting(i);
+    }
+    auto sum_demand = [&]() {
+        int64_t t = 0;
+        for (int64_t i : round) t += demand[i];
+        return t;
+    };
+    int64_t total = sum_demand();
+    int32_t alloc_case = total == avail ? KVCP_CASE_EQUAL : total < avail ? KVCP_CASE_LESS : KVCP_CASE_MORE;
+    if (alloc_case == KVCP_CASE_LESS) {
+        double min_rt = std::numeric_limits<double>::infinity();
+        for (int64_t i = 0; i < n; ++i)
+            if (d[i].in_batch) min_rt = std::min(min_rt, req[i].remaining_time);
+        for (; next_waiting < waiting_rest.size(); ++next_waiting) {
+            const int64_t i = waiting_rest[next_waiting];
+            if (total + total_demand(i) > avail) break;
+            const double t_iter = p->iter_time_base + p->iter_time_per_token * double(batch_tokens + req[i].prompt_len);
+            if (t_iter > std::min(min_rt, req[i].remaining_time)) break;
+            add_waiting(i);
+            min_rt = std::min(min_rt, req[i].remaining_time);
+            total = sum_demand();
+        }
+    }
+    // A new request must at least hold its prompt and one granule: one whose share is smaller is
+    // left out and the round is repeated without it.
+    int64_t excess = 0;
+    const int64_t round_avail = avail;
+    std::vector<int64_t> share(n, 0);
+    for (bool again = true; again && !round.empty();) {
+        again = false;
+        std::vector<int64_t> M(round.size()), sp(round.size()), A(round.size());
+        std::vector<double> RT(round.size());
+        for (size_t k = 0; k < round.size(); ++k) {
+            M[k] = demand[round[k]];
+            sp[k] = req[round[k]].prompt_len;
+            RT[k] = req[round[k]].remaining_time;
+        }
+        int64_t slack = 0;
+        if (kvcp_allocate(M.data(), RT.data(), sp.data(), int64_t(round.size()), round_avail, A.data(), &slack) != 0)
+            return -1;
+        excess = slack < 0 ? -slack : 0;
+        alloc_case = slack == 0 ? KVCP_CASE_EQUAL : slack > 0 ? KVCP_CASE_LESS : KVCP_CASE_MORE;
+        std::vector<int64_t> kept;
+        for (size_t k = 0; k < round.size(); ++k) {
+            const int64_t i = round[k];
+            share[i] = A[k];
+            if (req[i].state == KVCP_WAITING && d[i].host < 0 && d[i].grant + A[k] < req[i].prompt_len + B) {
+                batch_tokens -= req[i].prompt_len;
+                d[i].in_batch = 0;
+                share[i] = 0;
+                again = true;
+            } else {
+                kept.push_back(i);
+            }
+        }
+        round.swap(kept);
+    }
+    for (int64_t i : round) {
+        d[i].grant += share[i];
+        avail -= share[i];
+        d[i].shortfall = demand[i] - share[i];
+    }
+
+    // ---- 4. borrowing KVC that a running request releases before the borrower runs out
+    std::vector<char> lends(n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+        if (!d[i].in_batch || d[i].shortfall <= 0) continue;
+        const int64_t holds = req[i].allocated + d[i].grant;
+        const int64_t occupied = req[i].state == KVCP_WAITING ? req[i].prompt_len : req[i].used;
+        const int64_t runs_for = holds - occupied;  // iterations until it exhausts what it holds
+        int64_t best = -1, best_left = -1, best_amount = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (j == i || req[j].state != KVCP_RUNNING || !d[j].in_batch || lends[j]) continue;
+            const int64_t left = std::max<int64_t>(0, req[j].est_output_len - req[j].generated);
+            const int64_t amount = req[j].allocated + d[j].grant;
+            if (left > runs_for || amount < d[i].shortfall) continue;
+            if (best < 0 || left > best_left || (left == best_left && amount < best_amount)) {
+                best = j; best_left = left; best_amount = amount;
+            }
+        }
+        if (best >= 0) {
+            lends[best] = 1;
+            d[i].lender = best;
+        }
+    }
+
+    std::copy(d.begin(), d.end(), out);
+    if (summary) {
+        summary->unallocated_after = avail;
+        summary->basic_demand = D;
+        summary->excess = excess;
+        summary->batch_tokens = batch_tokens;
+        summary->n_preempted = n_preempted;
+        summary->alloc_case = alloc_case;
+    }
+    return 0;
+}
+
 }  // extern "C"
 
 struct kvcp_block_manager {

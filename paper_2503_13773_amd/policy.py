@@ -16,6 +16,38 @@ _i64, _f64, _i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int32
 _pi64, _pf64, _pi32 = ctypes.POINTER(_i64), ctypes.POINTER(_f64), ctypes.POINTER(_i32)
 
 
+WAITING, RUNNING = 0, 1
+KEEP, PREEMPT_SWAP, PREEMPT_RECOMPUTE = 0, 1, 2
+CASE_EQUAL, CASE_LESS, CASE_MORE = 0, 1, 2
+
+
+class Request(ctypes.Structure):
+    """kvcp_request"""
+    _fields_ = [("state", _i32), ("reserved", _i32), ("prompt_len", _i64), ("est_output_len", _i64),
+                ("generated", _i64), ("allocated", _i64), ("used", _i64), ("remaining_time", _f64),
+                ("tbt_slo", _f64)]
+
+
+class StepParams(ctypes.Structure):
+    """kvcp_step_params"""
+    _fields_ = [("unallocated", _i64), ("block_tokens", _i64), ("buffer_tokens", _i64),
+                ("token_budget", _i64), ("token_bucket", _i64), ("m", _i32), ("n_slo_edges", _i32),
+                ("slo_edges", _pf64), ("max_iteration_latency", _f64), ("eps", _f64),
+                ("iter_time_base", _f64), ("iter_time_per_token", _f64), ("sweet_spot", _f64)]
+
+
+class Decision(ctypes.Structure):
+    """kvcp_decision"""
+    _fields_ = [("in_batch", _i32), ("critical", _i32), ("preempt", _i32), ("proactive", _i32),
+                ("grant", _i64), ("host", _i64), ("s0", _i64), ("lender", _i64), ("shortfall", _i64)]
+
+
+class StepSummary(ctypes.Structure):
+    """kvcp_step_summary"""
+    _fields_ = [("unallocated_after", _i64), ("basic_demand", _i64), ("excess", _i64),
+                ("batch_tokens", _i64), ("n_preempted", _i32), ("alloc_case", _i32)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -39,6 +71,11 @@ def lib():
         "kvcp_preemption_order": (ctypes.c_int, [_pf64, _pi64, _pi64, _i64, _pf64, _i32, _i64, _pi64]),
         "kvcp_sweet_spot": (_f64, [_f64] * 7),
         "kvcp_choose_swap": (ctypes.c_int, [_f64, _f64]),
+        "kvcp_fit_linear": (ctypes.c_int, [_pf64, _pf64, _i64, _pf64, _pf64, _pf64]),
+        "kvcp_fit_power_law": (ctypes.c_int, [_pf64, _pf64, _i64, _pf64, _pf64, _pf64]),
+        "kvcp_schedule_step": (ctypes.c_int, [ctypes.POINTER(Request), _i64, ctypes.POINTER(StepParams),
+                                              ctypes.POINTER(Decision), ctypes.POINTER(StepSummary)]),
+        "kvcp_embedding_block_range": (ctypes.c_int, [_i64, _i64, _i64, _i64, _i64, _pi64, _pi64]),
         "kvcp_bm_create": (ctypes.c_void_p, [_i64, _i64]),
         "kvcp_bm_destroy": (None, [ctypes.c_void_p]),
         "kvcp_bm_free_general": (_i64, [ctypes.c_void_p]),
@@ -124,6 +161,55 @@ def sweet_spot(gamma_s: float, delta_s: float, alpha_r: float, beta_r: float, ka
 
 def choose_swap(seq_len: float, sweet_spot_: float) -> bool:
     return bool(lib().kvcp_choose_swap(seq_len, sweet_spot_))
+
+
+def fit_linear(x: Sequence[float], y: Sequence[float]) -> Tuple[float, float, float]:
+    """(gamma, delta, r2) of the least-squares line y = gamma x + delta (kvcp_fit_linear)."""
+    g, d, r2 = _f64(), _f64(), _f64()
+    if len(x) != len(y) or lib().kvcp_fit_linear(_arr(_f64, x), _arr(_f64, y), len(x), ctypes.byref(g),
+                                                 ctypes.byref(d), ctypes.byref(r2)) != 0:
+        raise ValueError("need at least two finite samples with distinct x")
+    return g.value, d.value, r2.value
+
+
+def fit_power_law(x: Sequence[float], y: Sequence[float]) -> Tuple[float, float, float]:
+    """(alpha, beta, r2) of y = alpha x^beta fitted in log-log space (kvcp_fit_power_law)."""
+    a, b, r2 = _f64(), _f64(), _f64()
+    if len(x) != len(y) or lib().kvcp_fit_power_law(_arr(_f64, x), _arr(_f64, y), len(x), ctypes.byref(a),
+                                                    ctypes.byref(b), ctypes.byref(r2)) != 0:
+        raise ValueError("need at least two positive samples with distinct x")
+    return a.value, b.value, r2.value
+
+
+def schedule_step(requests: Sequence[Request], *, unallocated: int, block_tokens: int = 8,
+                  buffer_tokens: int = 8, token_budget: int = 2048, token_bucket: int = 128, m: int = 2,
+                  slo_edges: Sequence[float] = (0.2, 0.5), max_iteration_latency: float = 0.0,
+                  eps: float = 0.0, iter_time_base: float = 0.0, iter_time_per_token: float = 0.0,
+                  sweet_spot: float = 0.0) -> Tuple[List[Decision], StepSummary]:
+    """kvcp_schedule_step: one decision per request (same order) and the step summary."""
+    n = len(requests)
+    reqs = (Request * max(n, 1))(*requests)
+    out = (Decision * max(n, 1))()
+    edges = _arr(_f64, slo_edges)
+    params = StepParams(unallocated=unallocated, block_tokens=block_tokens, buffer_tokens=buffer_tokens,
+                        token_budget=token_budget, token_bucket=token_bucket, m=m,
+                        n_slo_edges=len(list(slo_edges)),
+                        slo_edges=ctypes.cast(edges, _pf64) if edges is not None else None,
+                        max_iteration_latency=max_iteration_latency, eps=eps,
+                        iter_time_base=iter_time_base, iter_time_per_token=iter_time_per_token,
+                        sweet_spot=sweet_spot)
+    summary = StepSummary()
+    if lib().kvcp_schedule_step(reqs, n, ctypes.byref(params), out, ctypes.byref(summary)) != 0:
+        raise ValueError("kvcp_schedule_step rejected its arguments")
+    return [out[i] for i in range(n)], summary
+
+
+def embedding_block_range(s0: int, sp_i: int, so_i: int, block_size: int, host_blocks: int) -> Optional[Tuple[int, int]]:
+    """(first block, block count) inside the host's block list, or None when it does not fit."""
+    first, count = _i64(), _i64()
+    rc = lib().kvcp_embedding_block_range(s0, sp_i, so_i, block_size, host_blocks, ctypes.byref(first),
+                                          ctypes.byref(count))
+    return (int(first.value), int(count.value)) if rc == 0 else None
 
 
 class BlockManager:

@@ -20,21 +20,6 @@ from typing import Dict, List, Sequence, Tuple
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 
-def fit_power_law(S: Sequence[float], L: Sequence[float]) -> Tuple[float, float]:
-    """Least squares of log L = log alpha + beta log S: returns (alpha, beta)."""
-    if len(S) < 2 or len(S) != len(L) or min(S) <= 0 or min(L) <= 0:
-        raise ValueError("need at least two positive (S, L) samples")
-    xs = [math.log(s) for s in S]
-    ys = [math.log(l) for l in L]
-    n = len(xs)
-    mx, my = sum(xs) / n, sum(ys) / n
-    sxx = sum((x - mx) ** 2 for x in xs)
-    if sxx == 0:
-        raise ValueError("all sequence lengths are equal")
-    beta = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sxx
-    return math.exp(my - beta * mx), beta
-
-
 def causal_attention_flops(S: int, q_heads: int, head_dim: int) -> float:
     """QK^T and PV multiply-adds over the causal triangle: 4 * D * Hq * S (S + 1) / 2."""
     return 4.0 * head_dim * q_heads * S * (S + 1) / 2.0
@@ -46,6 +31,7 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
     import torch
 
     from . import binding as K
+    from . import policy
 
     gen = torch.Generator(device="cpu").manual_seed(seed)
     smax = max(seq_lens)
@@ -75,7 +61,7 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
         samples.append({"S": int(S), "layer_ms": ms, "all_layers_ms": ms * layers,
                         "tflops": fl / ms / 1e9, "frac_of_mfma_peak": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS})
     fit = [s for s in samples if s["S"] >= fit_from] if sum(s["S"] >= fit_from for s in samples) >= 2 else samples
-    alpha, beta = fit_power_law([s["S"] for s in fit], [s["all_layers_ms"] for s in fit])
+    alpha, beta, _ = policy.fit_power_law([s["S"] for s in fit], [s["all_layers_ms"] for s in fit])
     return {"fit_from": fit_from, "model": {"layers": layers, "q_heads": q_heads, "kv_heads": kv_heads, "head_dim": head_dim,
                       "block_size": block_size}, "samples": samples, "alpha_ms": alpha, "beta": beta}
 

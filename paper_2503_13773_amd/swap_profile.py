@@ -14,49 +14,7 @@ from __future__ import annotations
 
 import argparse
 import json
-import math
 from typing import Dict, List, Sequence, Tuple
-
-
-def fit_linear(S: Sequence[float], L: Sequence[float]) -> Tuple[float, float]:
-    """Least-squares line through (S_i, L_i): returns (gamma, delta) of L = gamma * S + delta."""
-    n = len(S)
-    if n < 2 or len(L) != n:
-        raise ValueError("need at least two (S, L) samples")
-    ms = sum(S) / n
-    ml = sum(L) / n
-    sxx = sum((s - ms) ** 2 for s in S)
-    if sxx == 0:
-        raise ValueError("all sequence lengths are equal")
-    gamma = sum((s - ms) * (l - ml) for s, l in zip(S, L)) / sxx
-    return gamma, ml - gamma * ms
-
-
-def r_squared(S: Sequence[float], L: Sequence[float], gamma: float, delta: float) -> float:
-    ml = sum(L) / len(L)
-    ss_tot = sum((l - ml) ** 2 for l in L)
-    ss_res = sum((l - (gamma * s + delta)) ** 2 for s, l in zip(S, L))
-    return 1.0 - ss_res / ss_tot if ss_tot > 0 else 1.0
-
-
-def sweet_spot(gamma_s: float, delta_s: float, alpha_r: float, beta_r: float, kappa_r: float = 0.0,
-               eps_r: float = 0.0, s_max: float = 1e7) -> float:
-    """Sequence length S_s with L_r(S_s) = L_s(S_s), L_r(S) = alpha_r S^beta_r + kappa_r S + eps_r
-    (Section 3.5): swapping is the faster strategy above it.  Bisection on [1, s_max]; returns
-    inf if recomputation stays cheaper over the whole range, 0 if swapping always wins."""
-    f = lambda s: (alpha_r * s ** beta_r + kappa_r * s + eps_r) - (gamma_s * s + delta_s)
-    lo, hi = 1.0, s_max
-    if f(lo) >= 0:
-        return 0.0
-    if f(hi) < 0:
-        return math.inf
-    for _ in range(200):
-        mid = 0.5 * (lo + hi)
-        if f(mid) < 0:
-            lo = mid
-        else:
-            hi = mid
-    return 0.5 * (lo + hi)
 
 
 def profile_swap(seq_lens: Sequence[int], *, layers: int = 32, kv_heads: int = 8, head_dim: int = 128,
@@ -71,6 +29,7 @@ def profile_swap(seq_lens: Sequence[int], *, layers: int = 32, kv_heads: int = 8
     import torch
 
     from . import binding as K
+    from . import policy
 
     planes = 2 * layers
     block_bytes = kv_heads * block_size * head_dim * elem_bytes
@@ -106,11 +65,11 @@ def profile_swap(seq_lens: Sequence[int], *, layers: int = 32, kv_heads: int = 8
                         "swap_in_ms": i, "swap_ms": o + i,
                         "out_GBs": nbytes / o / 1e6, "in_GBs": nbytes / i / 1e6})
     Ss = [s["S"] for s in samples]
-    gamma, delta = fit_linear(Ss, [s["swap_ms"] for s in samples])
+    gamma, delta, r2 = policy.fit_linear(Ss, [s["swap_ms"] for s in samples])
     return {"model": {"layers": layers, "kv_heads": kv_heads, "head_dim": head_dim, "block_size": block_size,
                       "bytes_per_token": 2 * layers * kv_heads * head_dim * elem_bytes},
             "samples": samples, "gamma_ms_per_token": gamma, "delta_ms": delta,
-            "r2": r_squared(Ss, [s["swap_ms"] for s in samples], gamma, delta)}
+            "r2": r2}
 
 
 def main() -> int:

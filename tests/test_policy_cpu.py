@@ -24,7 +24,7 @@ def built():
 def test_policy_library_exports_every_declared_symbol():
     text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "kvc_policy.h")).read(), flags=re.S)
     declared = set(re.findall(r"KVCP_API\s+[\w\s\*]+?\b(kvcp_\w+)\s*\(", text))
-    assert len(declared) == 18
+    assert len(declared) >= 22 and {'kvcp_schedule_step', 'kvcp_fit_linear', 'kvcp_fit_power_law'} <= declared
     out = subprocess.run(["nm", "-D", "--defined-only", P.library_path()], capture_output=True, text=True).stdout
     assert declared <= set(re.findall(r"\bT\s+(kvcp_\w+)", out))
     subprocess.check_call(["gcc", "-std=c99", "-fsyntax-only", "-x", "c", os.path.join(ROOT, "include", "kvc_policy.h")])
@@ -134,9 +134,9 @@ def test_strategy_selection_and_sweet_spot():
     assert P.choose_swap(want * 1.01, ss) and not P.choose_swap(want * 0.99, ss)
     assert P.sweet_spot(0.01, 0.0, 1.0, 2.0, eps_r=1.0) == 0.0
     assert P.sweet_spot(1.0, 10.0, 1e-12, 1.0) == math.inf
-    # agrees with the Python solver used by the swap profiler
-    from paper_2503_13773_amd.swap_profile import sweet_spot as py_ss
-    assert P.sweet_spot(0.0047, 0.145, 3e-7, 2.0, 0.002, 0.5) == pytest.approx(py_ss(0.0047, 0.145, 3e-7, 2.0, 0.002, 0.5), rel=1e-9)
+    # all four recompute terms, worked by hand: 2e-6 S^2 + 0.001 S + 0.5 = 0.005 S + 8.5 has the
+    # positive root S = 1000 (1 + sqrt 5)
+    assert P.sweet_spot(0.005, 8.5, 2e-6, 2.0, 0.001, 0.5) == pytest.approx(1000 * (1 + math.sqrt(5)), rel=1e-9)
 
 
 def test_block_manager_with_reserved_pool():
@@ -282,3 +282,142 @@ def test_padding_and_sweet_spot_properties():
         if 0 < ss < math.inf:
             assert a * ss ** b == pytest.approx(g * ss + d, rel=1e-6)      # the two regressors meet there
             assert a * (2 * ss) ** b > g * (2 * ss) + d                     # recompute loses beyond it
+
+
+# ---------------------------------------------------------------------------
+# one scheduler step (Sections 3.3.2, 3.3.3, 3.4, 3.5): every expectation below is worked by hand
+# ---------------------------------------------------------------------------
+def R(state, sp, so, gen=0, alloc=0, used=0, rt=1.0, slo=0.1):
+    return P.Request(state=state, reserved=0, prompt_len=sp, est_output_len=so, generated=gen,
+                     allocated=alloc, used=used, remaining_time=rt, tbt_slo=slo)
+
+
+STEP = dict(block_tokens=8, buffer_tokens=8, m=2, max_iteration_latency=0.05, eps=0.01)
+
+
+def row(d):
+    return (d.in_batch, d.critical, d.preempt, d.proactive, d.grant, d.host, d.s0, d.lender, d.shortfall)
+
+
+def test_step_critical_sets_basic_demand_embedding_and_the_case_with_room_left():
+    reqs = [R(P.RUNNING, 100, 50, gen=20, alloc=160, used=120, rt=0.5),    # 0 has 40 tokens of unused allocation
+            R(P.RUNNING, 40, 30, gen=24, alloc=64, used=64, rt=0.055),     # 1 used up its KVC, RT - T < eps: N_r
+            R(P.WAITING, 24, 16, rt=0.05),                                 # 2 critical waiting: N_w
+            R(P.WAITING, 16, 8, rt=2.0),                                   # 3 fits inside request 0
+            R(P.WAITING, 200, 100, rt=3.0)]                                # 4 too long for the token budget
+    dec, s = P.schedule_step(reqs, unallocated=200, token_budget=50, **STEP)
+    # request 2 cannot be embedded in 0: 160 - (120+16) - (24+16) = -16 < 8.  D = (24+8) + 8 = 40 <= 200: no
+    # preemption; basic grants 32 and 8.  Batch so far: two running (1 token each) + 24 prompt tokens = 26.
+    # Request 3 (prompt 16 -> 42 <= 50) is embedded in 0: 160 - (120+8) - (16+8) = 8 >= 8, s0 = 160-128-8 = 24.
+    # Request 4 (42 + 200 > 50) stays out.  Demands: request 2: 40 - 32 = 8; request 1: 70 - 64 - 8 < 0 -> 0;
+    # request 3: 0.  Sum 8 < 160: the case with room left; request 4's 300 does not fit either, so nothing is
+    # added and everybody gets its demand.
+    assert row(dec[0]) == (1, 0, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert row(dec[1]) == (1, 1, P.KEEP, 0, 8, -1, 0, -1, 0)
+    assert row(dec[2]) == (1, 1, P.KEEP, 0, 40, -1, 0, -1, 0)
+    assert row(dec[3]) == (1, 0, P.KEEP, 0, 0, 0, 24, -1, 0)
+    assert row(dec[4]) == (0, 0, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert (s.unallocated_after, s.basic_demand, s.excess, s.batch_tokens, s.n_preempted, s.alloc_case) == \
+        (152, 40, 0, 42, 0, P.CASE_LESS)
+
+
+@pytest.mark.parametrize("sweet,strategy", [(100.0, P.PREEMPT_RECOMPUTE), (40.0, P.PREEMPT_SWAP)])
+def test_step_preempts_in_policy_order_until_the_basic_demand_fits(sweet, strategy):
+    reqs = [R(P.RUNNING, 50, 400, gen=10, alloc=100, used=60, slo=0.1),    # 0 tight TBT SLO: last to be preempted
+            R(P.RUNNING, 300, 300, gen=50, alloc=400, used=350, slo=1.0),  # 1 loose SLO, 250 tokens left (bucket 1)
+            R(P.RUNNING, 30, 300, gen=20, alloc=64, used=50, slo=1.0),     # 2 loose SLO, 280 tokens left (bucket 2)
+            R(P.WAITING, 60, 20, rt=0.05)]                                 # 3 critical: needs 60 + 8 = 68
+    dec, s = P.schedule_step(reqs, unallocated=10, token_budget=1000, sweet_spot=sweet, **STEP)
+    # No host has room for request 3.  D = 68 > 10: victims in the order loosest SLO, then longest remaining
+    # time: request 2 first.  Its 64 tokens make 74 >= 68, so request 1 is spared.  Request 2 occupies 50
+    # tokens: recomputed when the sweet spot is 100, swapped when it is 40.
+    # Request 3 gets 68 (6 left), still misses 80 - 68 = 12 > 6: amortised alone it takes the 6, shortfall 6.
+    # It would run 74 - 60 = 14 iterations on what it holds; requests 0 and 1 finish far later: no lender.
+    assert row(dec[2]) == (0, 0, strategy, 0, 0, -1, 0, -1, 0)
+    assert row(dec[1]) == (1, 0, P.KEEP, 0, 0, -1, 0, -1, 0) and row(dec[0]) == (1, 0, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert row(dec[3]) == (1, 1, P.KEEP, 0, 74, -1, 0, -1, 6)
+    assert (s.unallocated_after, s.basic_demand, s.excess, s.batch_tokens, s.n_preempted, s.alloc_case) == \
+        (0, 68, 6, 62, 1, P.CASE_MORE)
+
+
+def test_step_amortises_adds_the_proactive_request_and_finds_a_lender():
+    reqs = [R(P.RUNNING, 20, 10, gen=8, alloc=29, used=28, rt=2.0),    # 0 unfulfilled (29 < 30), 2 iterations left: proactive
+            R(P.RUNNING, 50, 30, gen=27, alloc=80, used=77, rt=2.0),   # 1 fulfilled, finishes in 3 iterations
+            R(P.WAITING, 40, 60, rt=2.0),                              # 2
+            R(P.WAITING, 10, 90, rt=6.0)]                              # 3
+    dec, s = P.schedule_step(reqs, unallocated=96, token_budget=1000, **STEP)
+    # Nobody is critical.  Demands: request 0: 30 - 29 = 1; requests 2 and 3: 100 each; 201 > 96.
+    # Weights RT/sum RT * sp/sum sp with sum RT = 10, sum sp = 70: 2/9, 4/9, 3/9 of 96 -> 21 (capped at 1), 42, 32.
+    # Request 2 cannot hold its prompt plus a granule (42 < 48): it is left out and the round repeats with
+    # requests 0 and 3: sum RT = 8, sum sp = 30, shares 0.4 and 0.6 of 96 -> 38 (capped at 1) and 57.
+    # E_kvc = 101 - 96 = 5.  Request 3 misses 43; it runs 57 - 10 = 47 iterations on its 57 tokens.  Request 1
+    # finishes in 3 <= 47 iterations and holds 80 >= 43: the lender.  Request 0 holds only 30.
+    assert row(dec[0]) == (1, 0, P.KEEP, 1, 1, -1, 0, -1, 0)
+    assert row(dec[1]) == (1, 0, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert row(dec[2]) == (0, 0, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert row(dec[3]) == (1, 0, P.KEEP, 0, 57, -1, 0, 1, 43)
+    assert (s.unallocated_after, s.basic_demand, s.excess, s.batch_tokens, s.n_preempted, s.alloc_case) == \
+        (38, 0, 5, 12, 0, P.CASE_MORE)
+
+
+def test_step_adds_waiting_requests_while_kvc_and_slos_allow():
+    reqs = [R(P.RUNNING, 10, 10, gen=2, alloc=20, used=12, rt=0.5),
+            R(P.WAITING, 30, 10, rt=1.0), R(P.WAITING, 40, 10, rt=2.0), R(P.WAITING, 50, 10, rt=3.0),
+            R(P.WAITING, 20, 10, rt=4.0)]
+    kw = dict(STEP, iter_time_base=0.1, iter_time_per_token=0.004)
+    # token budget 35: the running request (1) + request 1 (30) = 31; request 2 would make 71.  Demand 40 < 200:
+    # requests are added in RT order while M_i fits and the modelled iteration stays below every RT in the
+    # batch: request 2 -> 71 tokens, 0.1 + 0.284 = 0.384 <= 0.5 fine, sum 90; request 3 -> 121 tokens, 0.584 > 0.5:
+    # stop (request 4 is not looked at: the queue is taken in order).
+    dec, s = P.schedule_step(reqs, unallocated=200, token_budget=35, **kw)
+    assert [d.in_batch for d in dec] == [1, 1, 1, 0, 0] and [d.grant for d in dec] == [0, 40, 50, 0, 0]
+    assert (s.unallocated_after, s.batch_tokens, s.alloc_case) == (110, 71, P.CASE_LESS)
+    # with 85 tokens of KVC request 2 no longer fits after request 1 (40 + 50 > 85) and stays out
+    dec, s = P.schedule_step(reqs, unallocated=85, token_budget=35, **kw)
+    assert [d.in_batch for d in dec] == [1, 1, 0, 0, 0] and s.unallocated_after == 45
+    # exactly enough: the case sum M = A'
+    dec, s = P.schedule_step(reqs, unallocated=40, token_budget=35, **kw)
+    assert s.alloc_case == P.CASE_EQUAL and dec[1].grant == 40 and s.unallocated_after == 0
+
+
+def test_step_returned_request_beyond_its_estimate_asks_for_one_granule():
+    # used up its allocation, not time-critical (N'_r), already 4 tokens past sp + so: demand B
+    reqs = [R(P.RUNNING, 10, 5, gen=9, alloc=19, used=19, rt=1.0)]
+    dec, s = P.schedule_step(reqs, unallocated=100, token_budget=10, **STEP)
+    assert row(dec[0]) == (1, 0, P.KEEP, 0, 8, -1, 0, -1, 0) and s.unallocated_after == 92
+    # the same request when time-critical gets its granule in the critical phase: D = B
+    reqs[0].remaining_time = 0.055
+    dec, s = P.schedule_step(reqs, unallocated=100, token_budget=10, **STEP)
+    assert row(dec[0]) == (1, 1, P.KEEP, 0, 8, -1, 0, -1, 0) and s.basic_demand == 8
+
+
+def test_step_hosts_take_one_guest_and_are_not_preempted():
+    reqs = [R(P.RUNNING, 10, 300, gen=10, alloc=320, used=20, slo=1.0),    # 0: roomy, loosest SLO
+            R(P.WAITING, 20, 10, rt=0.05), R(P.WAITING, 20, 10, rt=0.05)]  # two critical requests
+    dec, s = P.schedule_step(reqs, unallocated=0, token_budget=100, **STEP)
+    # the first critical request (same basic requirement: index order) is embedded: s0 = 320 - (20+10) - 8 = 282;
+    # the second finds the host taken, needs 28 from an empty pool, and the only running request is a host:
+    # nobody can be preempted, it waits
+    assert row(dec[1]) == (1, 1, P.KEEP, 0, 0, 0, 282, -1, 0)
+    assert row(dec[2]) == (0, 1, P.KEEP, 0, 0, -1, 0, -1, 0)
+    assert dec[0].preempt == P.KEEP and s.n_preempted == 0 and s.basic_demand == 28
+
+
+def test_step_rejects_bad_arguments_and_accepts_an_empty_queue():
+    dec, s = P.schedule_step([], unallocated=5, **STEP)
+    assert dec == [] and s.unallocated_after == 5
+    for bad in [R(P.WAITING, 0, 5), R(P.WAITING, 5, 0), R(P.WAITING, 5, 5, alloc=8), R(P.RUNNING, 5, 5, alloc=4, used=6),
+                R(P.RUNNING, 5, 5, rt=0.0), R(7, 5, 5)]:
+        with pytest.raises(ValueError):
+            P.schedule_step([bad], unallocated=10, **STEP)
+    with pytest.raises(ValueError):
+        P.schedule_step([R(P.WAITING, 5, 5)], unallocated=-1, **STEP)
+
+
+def test_embedding_block_range_rounds_to_whole_blocks():
+    # s0 = 24 tokens, guest of 16 + 8 tokens, 16-token blocks: starts at block ceil(24/16) = 2, spans 2 blocks
+    assert P.embedding_block_range(24, 16, 8, 16, 10) == (2, 2)
+    assert P.embedding_block_range(24, 16, 8, 16, 4) == (2, 2)
+    assert P.embedding_block_range(24, 16, 8, 16, 3) is None        # rounding pushes it past the host's blocks
+    assert P.embedding_block_range(32, 1, 0, 16, 3) == (2, 1)
+    assert P.embedding_block_range(-1, 1, 0, 16, 3) is None
