@@ -41,8 +41,10 @@ KVCP_API double kvcp_estimated_output_len(double predicted, double range, double
 
 /* Request i (prompt sp_i, estimated output so_i) fits into running request j's allocated but
  * unused KVC (allocated a_j, used u_j) iff a_j - (u_j + so_i) - (sp_i + so_i) >= b.
- * Returns 1 and stores the start offset s0 = a_j - (u_j + so_i) - b (tokens from the start of
- * r_j's allocation) when it fits, else 0 (s0 untouched).  s0 may be NULL. */
+ * Returns 1 and stores s0 = a_j - (u_j + so_i) - b when it fits, else 0 (s0 untouched; s0 may be
+ * NULL).  s0 is the printed quantity: the room left for r_i once r_j's own growth over the next
+ * so_i iterations and the buffer b are set aside.  r_i's space therefore begins a_j - s0 =
+ * u_j + so_i + b tokens into r_j's allocation: after so_i iterations r_j stands b tokens before it. */
 KVCP_API int kvcp_embedding_fits(int64_t a_j, int64_t u_j, int64_t sp_i, int64_t so_i, int64_t b,
                                  int64_t *s0);
 
@@ -151,7 +153,8 @@ typedef struct {
     int32_t proactive;  /* 1: joined the allocation round through the m-iteration rule */
     int64_t grant;      /* KVC tokens newly allocated to it out of the unallocated KVC */
     int64_t host;       /* index of the running request it is embedded in, else -1 */
-    int64_t s0;         /* start offset inside the host's allocation in tokens (host >= 0 only) */
+    int64_t s0;         /* the s0 of kvcp_embedding_fits (host >= 0 only): its space begins a_host - s0
+                           tokens into the host's allocation */
     int64_t lender;     /* index of the running request whose released KVC it will use for its
                            shortfall, else -1 */
     int64_t shortfall;  /* part of its total demand M_i covered neither by its allocation, its grant
@@ -174,7 +177,9 @@ typedef struct {
  *      waiting requests with RT - T_I^max < eps are critical (N_w).
  *   2. Critical requests, in descending order of their basic requirement (s^p_i + B waiting, B
  *      returned): a waiting one is first tried with the embedding method (host = running request
- *      with unused allocation and the least of it that fits; a host takes one guest per step);
+ *      with unused allocation and the least of it that fits, also after rounding the guest's
+ *      space to whole granules of B tokens, see kvcp_embedding_block_range; a host takes one
+ *      guest per step);
  *      the others need D_kvc of unallocated KVC.  While A'_kvc < D_kvc, running requests that are
  *      neither critical nor hosts are preempted in the order of Section 3.4, each by swapping if
  *      its occupied KVC exceeds the sweet spot and by recomputation otherwise (Section 3.5); a
@@ -202,12 +207,14 @@ typedef struct {
 KVCP_API int kvcp_schedule_step(const kvcp_request *req, int64_t n, const kvcp_step_params *params,
                                 kvcp_decision *out, kvcp_step_summary *summary);
 
-/* Blocks of the host's block list an embedded request occupies: it starts at the first block
- * boundary at or after token offset s0 and spans ceil((sp_i + so_i) / block_size) blocks, so guest
- * and host never share a block.  Returns 0 and stores first / count, or -1 when rounding to
- * blocks pushes it past the host's host_blocks blocks. */
-KVCP_API int kvcp_embedding_block_range(int64_t s0, int64_t sp_i, int64_t so_i, int64_t block_size,
-                                        int64_t host_blocks, int64_t *first, int64_t *count);
+/* Blocks of the host's block list an embedded request occupies: its space begins a_j - s0 tokens
+ * into the host's allocation (see kvcp_embedding_fits); it starts at the first block boundary at
+ * or after that and spans ceil((sp_i + so_i) / block_size) blocks, so guest and host never share a
+ * block.  Returns 0 and stores first / count, or -1 when rounding to blocks pushes it past the
+ * host's host_blocks blocks. */
+KVCP_API int kvcp_embedding_block_range(int64_t a_j, int64_t s0, int64_t sp_i, int64_t so_i,
+                                        int64_t block_size, int64_t host_blocks, int64_t *first,
+                                        int64_t *count);
 
 /* ---- block manager with a globally reserved pool (Section 3.3.3) ---- */
 

@@ -199,10 +199,12 @@ int kvcp_fit_power_law(const double *x, const double *y, int64_t n, double *alph
     return 0;
 }
 
-int kvcp_embedding_block_range(int64_t s0, int64_t sp_i, int64_t so_i, int64_t block_size,
+int kvcp_embedding_block_range(int64_t a_j, int64_t s0, int64_t sp_i, int64_t so_i, int64_t block_size,
                                int64_t host_blocks, int64_t *first, int64_t *count) {
-    if (s0 < 0 || sp_i < 0 || so_i < 0 || block_size <= 0 || host_blocks < 0 || !first || !count) return -1;
-    const int64_t f = (s0 + block_size - 1) / block_size;
+    if (a_j < 0 || s0 < 0 || s0 > a_j || sp_i < 0 || so_i < 0 || block_size <= 0 || host_blocks < 0 || !first ||
+        !count)
+        return -1;
+    const int64_t f = (a_j - s0 + block_size - 1) / block_size;
     const int64_t c = (sp_i + so_i + block_size - 1) / block_size;
     if (f + c > host_blocks) return -1;
     *first = f;
@@ -267,6 +269,10 @@ int kvcp_schedule_step(const kvcp_request *req, int64_t n, const kvcp_step_param
             int64_t s0;
             if (!kvcp_embedding_fits(req[j].allocated, req[j].used, req[i].prompt_len, req[i].est_output_len,
                                      p->buffer_tokens, &s0))
+                continue;
+            int64_t first, count;  // KVC is handed out in granules of B tokens: the guest must fit in whole ones
+            if (kvcp_embedding_block_range(req[j].allocated, s0, req[i].prompt_len, req[i].est_output_len, B,
+                                           req[j].allocated / B, &first, &count) != 0)
                 continue;
             const int64_t rem = req[j].allocated - req[j].used;
             if (best < 0 || rem < best_rem) { best = j; best_rem = rem; best_s0 = s0; }

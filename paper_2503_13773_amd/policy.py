@@ -75,7 +75,7 @@ def lib():
         "kvcp_fit_power_law": (ctypes.c_int, [_pf64, _pf64, _i64, _pf64, _pf64, _pf64]),
         "kvcp_schedule_step": (ctypes.c_int, [ctypes.POINTER(Request), _i64, ctypes.POINTER(StepParams),
                                               ctypes.POINTER(Decision), ctypes.POINTER(StepSummary)]),
-        "kvcp_embedding_block_range": (ctypes.c_int, [_i64, _i64, _i64, _i64, _i64, _pi64, _pi64]),
+        "kvcp_embedding_block_range": (ctypes.c_int, [_i64, _i64, _i64, _i64, _i64, _i64, _pi64, _pi64]),
         "kvcp_bm_create": (ctypes.c_void_p, [_i64, _i64]),
         "kvcp_bm_destroy": (None, [ctypes.c_void_p]),
         "kvcp_bm_free_general": (_i64, [ctypes.c_void_p]),
@@ -109,7 +109,7 @@ def estimated_output_len(predicted: float, range_: float, confidence_: float, un
 
 
 def embedding_fits(a_j: int, u_j: int, sp_i: int, so_i: int, b: int) -> Optional[int]:
-    """Start offset s0 inside r_j's allocation when request i fits, else None."""
+    """s0 (the room left for request i inside r_j's allocation) when it fits, else None."""
     s0 = _i64()
     return int(s0.value) if lib().kvcp_embedding_fits(a_j, u_j, sp_i, so_i, b, ctypes.byref(s0)) else None
 
@@ -204,10 +204,11 @@ def schedule_step(requests: Sequence[Request], *, unallocated: int, block_tokens
     return [out[i] for i in range(n)], summary
 
 
-def embedding_block_range(s0: int, sp_i: int, so_i: int, block_size: int, host_blocks: int) -> Optional[Tuple[int, int]]:
+def embedding_block_range(a_j: int, s0: int, sp_i: int, so_i: int, block_size: int,
+                          host_blocks: int) -> Optional[Tuple[int, int]]:
     """(first block, block count) inside the host's block list, or None when it does not fit."""
     first, count = _i64(), _i64()
-    rc = lib().kvcp_embedding_block_range(s0, sp_i, so_i, block_size, host_blocks, ctypes.byref(first),
+    rc = lib().kvcp_embedding_block_range(a_j, s0, sp_i, so_i, block_size, host_blocks, ctypes.byref(first),
                                           ctypes.byref(count))
     return (int(first.value), int(count.value)) if rc == 0 else None
 

@@ -1,167 +1,30 @@
-"""A miniature serving loop: the host-side policy core (block manager with reserved pool,
-preemption order, swap-or-recompute choice) drives the three device calls (kv_cache_append,
-paged_attention_decode, kv_block_copy to pinned host memory) over several iterations under KV
-pressure.  Every iteration's attention output is checked against the oracle run on a host
-mirror of the cache, so a wrong block table, a lost swap or a stale block shows up at once."""
-import numpy as np
+"""The serving loop on the MI355X: every scheduling decision comes from kvcp_schedule_step (the
+policy core in C++), the server (paper_2503_13773_amd.serving) turns the decisions into the device calls of the
+C ABI - kv_cache_append, paged_attention_decode, paged_attention_prefill for admissions and
+recomputation, kv_block_copy to and from pinned host memory for swapping - and every attention
+output of every iteration is compared with the oracle's attention over the request's true token
+sequence (independent of the server's block tables and of what its swaps and recomputations left
+in the cache).  The scenario (tests/serving_scenario.py) contains a victim above the sweet spot
+(swapped out and back in), victims below it (dropped and recomputed through the prefill kernel), a
+request embedded in another's unused allocation, and the host's overrun into its guest."""
 import pytest
-import torch
 
-import kvc_workloads as W
-from gpu_util import BF16_TOL, dev_tensor, out_to_f64
+import serving_scenario as S
+from gpu_util import BF16_TOL
 
 pytestmark = pytest.mark.gpu
 
-HQ, HKV, D, BS = 8, 2, 128, 16
 
-
-def bf16_rand(rng, shape):
-    return W.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
-
-
-def test_policy_driven_decode_loop_with_swap_preemption(oracle_mod):
-    import paper_2503_13773_amd as K
-    from paper_2503_13773_amd import policy as P
-
-    rng = np.random.default_rng(2024)
-    NB, RESERVED, LMAX = 17, 2, 8                      # 15 general blocks of 16 tokens against a peak demand of 20
-    bm = P.BlockManager(NB, RESERVED)
-    sweet = P.sweet_spot(0.0047, 0.145, 1e-3, 2.0)     # a low sweet spot: every victim here is swapped
-    assert sweet < 16
-
-    # requests: (prompt length, true output length, TBT SLO)
-    specs = [(40, 30, 0.1), (25, 40, 1.0), (60, 25, 0.6), (18, 35, 1.5), (33, 20, 0.3)]
-    n = len(specs)
-    hk = np.zeros((NB, HKV, BS, D), dtype=np.uint16)   # host mirror of the device cache
-    hv = np.zeros_like(hk)
-    dk, dv = dev_tensor(hk, W.BF16), dev_tensor(hv, W.BF16)
-    host_pool = torch.zeros((2, 16, HKV, BS, D), dtype=torch.bfloat16, pin_memory=True)  # swap space: 16 blocks
-    host_free = list(range(16))
-    tables = np.full((n, LMAX), -1, dtype=np.int32)
-    lens = np.zeros(n, dtype=np.int32)
-    state = ["waiting"] * n                            # waiting / running / swapped / done
-    swapped_slots = {}
-    produced = np.zeros(n, dtype=np.int64)
-    q_all = bf16_rand(rng, (n, HQ, D))
-    stats = dict(preemptions=0, swap_ins=0, reserved_used=0, steps=0)
-
-    def blocks_of(i):
-        return [int(b) for b in tables[i, :(lens[i] + BS - 1) // BS]]
-
-    def append_tokens(ids, k_new, v_new, pos):
-        """Write one token for each request in ids on the device and in the mirror."""
-        t = np.full((len(ids), LMAX), -1, dtype=np.int32)
-        t[:] = tables[ids]
-        oracle_mod.kv_cache_append(k_new, v_new, hk, hv, t, pos)
-        K.kv_cache_append(dev_tensor(k_new, W.BF16), dev_tensor(v_new, W.BF16), dk, dv,
-                          torch.from_numpy(t).cuda(), torch.from_numpy(pos).cuda())
-
-    def grow(i):
-        """Make sure request i owns the block its next token falls into; False on failure."""
-        if lens[i] % BS:
-            return True
-        got = bm.allocate(1)
-        if got is None:
-            got = bm.allocate_reserved(1)              # global reservation serves allocation failures
-            if got is not None:
-                stats["reserved_used"] += 1
-        if got is None:
-            return False
-        tables[i, lens[i] // BS] = got[0]
-        return True
-
-    def swap_out(i):
-        ids = blocks_of(i)
-        slots = [host_free.pop() for _ in ids]
-        mp = torch.tensor(list(zip(ids, slots)), dtype=torch.int64).cuda()
-        pool = torch.stack([dk, dv])                   # [2][NB]... a copy; copy back the planes afterwards is not needed for swap-out
-        K.kv_block_copy(pool, host_pool, mp)
-        torch.cuda.synchronize()
-        hk[ids] = 0x7FC0                               # the freed blocks are poisoned on both sides
-        hv[ids] = 0x7FC0
-        dk[torch.tensor(ids).cuda()] = float("nan")
-        dv[torch.tensor(ids).cuda()] = float("nan")
-        bm.release(ids)
-        swapped_slots[i] = slots
-        state[i] = "swapped"
-        stats["preemptions"] += 1
-
-    def swap_in(i):
-        slots = swapped_slots[i]
-        ids = bm.allocate(len(slots))
-        if ids is None:
-            return False
-        pool = torch.stack([dk, dv])
-        mp = torch.tensor(list(zip(slots, ids)), dtype=torch.int64).cuda()
-        K.kv_block_copy(host_pool, pool, mp)
-        torch.cuda.synchronize()
-        dk.copy_(pool[0]); dv.copy_(pool[1])
-        hp = host_pool.view(torch.int16).numpy().view(np.uint16)
-        hk[ids] = hp[0, slots]
-        hv[ids] = hp[1, slots]
-        tables[i, :len(ids)] = ids
-        host_free.extend(slots)
-        del swapped_slots[i]
-        state[i] = "running"
-        stats["swap_ins"] += 1
-        return True
-
-    for step in range(70):
-        # admit waiting requests while their prompt fits (prompt KV is written token by token)
-        for i in range(n):
-            if state[i] == "waiting":
-                need = (specs[i][0] + BS - 1) // BS
-                ids = bm.allocate(need)
-                if ids is None:
-                    continue
-                tables[i, :need] = ids
-                for t in range(specs[i][0]):
-                    append_tokens([i], bf16_rand(rng, (1, HKV, D)), bf16_rand(rng, (1, HKV, D)),
-                                  np.array([t], dtype=np.int32))
-                lens[i] = specs[i][0]
-                state[i] = "running"
-        for i in list(swapped_slots):
-            swap_in(i)
-
-        running = [i for i in range(n) if state[i] == "running"]
-        if not running and all(s == "done" for s in state):
-            break
-        # every running request needs room for its next token; on failure preempt by the policy order
-        blocked = [i for i in running if not grow(i)]
-        while blocked:
-            cand = [i for i in running if state[i] == "running"]
-            order = P.preemption_order([specs[i][2] for i in cand],
-                                       [specs[i][1] - int(produced[i]) for i in cand],
-                                       [int(lens[i]) for i in cand])
-            victim = cand[order[0]]
-            assert P.choose_swap(float(lens[victim]), sweet)
-            swap_out(victim)
-            blocked = [i for i in running if state[i] == "running" and not grow(i)]
-        running = [i for i in running if state[i] == "running"]
-        if not running:
-            continue
-
-        # one decode iteration: append the new token of every running request, then attend
-        pos = lens[running].astype(np.int32)
-        append_tokens(running, bf16_rand(rng, (len(running), HKV, D)), bf16_rand(rng, (len(running), HKV, D)), pos)
-        lens[running] += 1
-        t_run = np.ascontiguousarray(tables[running])
-        l_run = np.ascontiguousarray(lens[running])
-        out = K.paged_attention_decode(dev_tensor(np.ascontiguousarray(q_all[running]), W.BF16), dk, dv,
-                                       torch.from_numpy(t_run).cuda(), torch.from_numpy(l_run).cuda(),
-                                       1.0 / np.sqrt(D))
-        torch.cuda.synchronize()
-        ref = oracle_mod.paged_attention_decode(np.ascontiguousarray(q_all[running]), hk, hv, t_run, l_run,
-                                                1.0 / np.sqrt(D), dtype="bf16")
-        assert np.abs(out_to_f64(out) - ref).max() <= BF16_TOL, step
-        stats["steps"] += 1
-        for i in running:
-            produced[i] += 1
-            if produced[i] >= specs[i][1]:
-                bm.release(blocks_of(i))
-                state[i] = "done"
-
-    print("[policy loop]", stats, flush=True)
-    assert all(s == "done" for s in state)
-    assert stats["preemptions"] >= 1 and stats["swap_ins"] == stats["preemptions"]
-    assert bm.free_general == NB - RESERVED and bm.free_reserved == RESERVED   # everything was returned
+def test_policy_core_drives_the_device_calls(oracle_mod):
+    from paper_2503_13773_amd.serving import HipOps
+    ops = HipOps(S.NUM_BLOCKS, S.SWAP_BLOCKS, S.HQ, S.HKV, S.D, S.BS)
+    srv = S.make_server(ops)
+    log = S.run(srv, oracle_mod, tol=BF16_TOL, verbose=True)
+    st = srv.stats
+    print("[serving]", st, flush=True)
+    assert srv.all_done()
+    assert st["swapped"] >= 1 and st["swap_ins"] == st["swapped"]          # above the sweet spot: swapped
+    assert st["recomputed"] >= 1 and any("recompute" in e and "preempt" not in e for e in log)   # below: prefill again
+    assert st["embedded"] >= 1 and st["overruns"] >= 1                     # embedding method and its failure mode
+    assert srv.bm.free_general == S.NUM_BLOCKS - S.RESERVED and srv.bm.free_reserved == S.RESERVED
+    assert sorted(srv.swap_free) == list(range(S.SWAP_BLOCKS))

@@ -308,7 +308,8 @@ def test_step_critical_sets_basic_demand_embedding_and_the_case_with_room_left()
     dec, s = P.schedule_step(reqs, unallocated=200, token_budget=50, **STEP)
     # request 2 cannot be embedded in 0: 160 - (120+16) - (24+16) = -16 < 8.  D = (24+8) + 8 = 40 <= 200: no
     # preemption; basic grants 32 and 8.  Batch so far: two running (1 token each) + 24 prompt tokens = 26.
-    # Request 3 (prompt 16 -> 42 <= 50) is embedded in 0: 160 - (120+8) - (16+8) = 8 >= 8, s0 = 160-128-8 = 24.
+    # Request 3 (prompt 16 -> 42 <= 50) is embedded in 0: 160 - (120+8) - (16+8) = 8 >= 8, s0 = 160-128-8 = 24
+    # (its space begins 160 - 24 = 136 tokens into request 0's allocation).
     # Request 4 (42 + 200 > 50) stays out.  Demands: request 2: 40 - 32 = 8; request 1: 70 - 64 - 8 < 0 -> 0;
     # request 3: 0.  Sum 8 < 160: the case with room left; request 4's 300 does not fit either, so nothing is
     # added and everybody gets its demand.
@@ -395,7 +396,8 @@ def test_step_hosts_take_one_guest_and_are_not_preempted():
     reqs = [R(P.RUNNING, 10, 300, gen=10, alloc=320, used=20, slo=1.0),    # 0: roomy, loosest SLO
             R(P.WAITING, 20, 10, rt=0.05), R(P.WAITING, 20, 10, rt=0.05)]  # two critical requests
     dec, s = P.schedule_step(reqs, unallocated=0, token_budget=100, **STEP)
-    # the first critical request (same basic requirement: index order) is embedded: s0 = 320 - (20+10) - 8 = 282;
+    # the first critical request (same basic requirement: index order) is embedded: s0 = 320 - (20+10) - 8 = 282
+    # (it starts 38 tokens in, 8 past where request 0 will stand after 10 more iterations);
     # the second finds the host taken, needs 28 from an empty pool, and the only running request is a host:
     # nobody can be preempted, it waits
     assert row(dec[1]) == (1, 1, P.KEEP, 0, 0, 0, 282, -1, 0)
@@ -415,9 +417,11 @@ def test_step_rejects_bad_arguments_and_accepts_an_empty_queue():
 
 
 def test_embedding_block_range_rounds_to_whole_blocks():
-    # s0 = 24 tokens, guest of 16 + 8 tokens, 16-token blocks: starts at block ceil(24/16) = 2, spans 2 blocks
-    assert P.embedding_block_range(24, 16, 8, 16, 10) == (2, 2)
-    assert P.embedding_block_range(24, 16, 8, 16, 4) == (2, 2)
-    assert P.embedding_block_range(24, 16, 8, 16, 3) is None        # rounding pushes it past the host's blocks
-    assert P.embedding_block_range(32, 1, 0, 16, 3) == (2, 1)
-    assert P.embedding_block_range(-1, 1, 0, 16, 3) is None
+    # host: 160 tokens allocated, 120 used; guest 16 + 8: s0 = 160 - (120+8) - 8 = 24 tokens of room, so the
+    # guest's space begins 160 - 24 = 136 tokens in (= u_j + so_i + b); 16-token blocks: block ceil(136/16) = 9,
+    # spanning ceil(24/16) = 2 blocks; the host has 10 blocks: 9 + 2 > 10 does not fit once rounded
+    assert P.embedding_block_range(160, 24, 16, 8, 16, 10) is None
+    assert P.embedding_block_range(160, 40, 16, 8, 16, 10) == (8, 2)     # begins at token 120 = block 7.5 -> 8
+    assert P.embedding_block_range(160, 48, 16, 8, 16, 10) == (7, 2)     # begins at token 112 = block 7
+    assert P.embedding_block_range(64, 32, 1, 0, 16, 4) == (2, 1)
+    assert P.embedding_block_range(64, 65, 1, 0, 16, 4) is None           # s0 cannot exceed the allocation
