@@ -20,19 +20,24 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kvc_oracle.c")
-_LIB = os.path.join(_HERE, "libkvc_oracle.so")
+# KVC_ORACLE_LIBRARY points at another build of the same source (the sanitizer run of the tests)
+_LIB = os.environ.get("KVC_ORACLE_LIBRARY") or os.path.join(_HERE, "libkvc_oracle.so")
 _DT = {"f32": 0, "bf16": 1, "f64": 2}
 _NP = {"f32": np.float32, "bf16": np.uint16, "f64": np.float64}
 _lib = None
 
 
-def build(force: bool = False) -> str:
+def build(force: bool = False, out: Optional[str] = None, extra_flags: Sequence[str] = ()) -> str:
     """Compile the oracle with gcc (about a second) when the library is missing or older than
-    its source.  Starts a child process: call it before anything in the process touches the GPU."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
-                               "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+    its source.  Starts a child process: call it before anything in the process touches the GPU.
+    `out` / `extra_flags` build a variant elsewhere (e.g. with sanitizers) and leave _LIB alone."""
+    target = out or _LIB
+    if out is None and os.environ.get("KVC_ORACLE_LIBRARY"):
+        return target                  # a library somebody else built: used as it is
+    if force or not os.path.exists(target) or os.path.getmtime(target) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", *extra_flags,
+                               "-o", target, _SRC, "-lm"])
+    return target
 
 
 def _load():

@@ -58,17 +58,19 @@ def build_library(extra_flags=(), verbose: bool = False) -> str:
 POLICY_LIB = os.path.join(PKG, "libkvc_policy.so")
 
 
-def build_policy_library(verbose: bool = False) -> str:
-    """The host-side policy core (plain C++, no GPU code)."""
-    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-fvisibility=hidden", "-Wall", "-Werror",
+def build_policy_library(verbose: bool = False, out: str = "", extra_flags=()) -> str:
+    """The host-side policy core (plain C++, no GPU code).  `out` / `extra_flags` build a variant
+    elsewhere (the sanitizer run of the CPU tests)."""
+    target = out or POLICY_LIB
+    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-fvisibility=hidden", "-Wall", "-Werror", *extra_flags,
            "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "policy", "kvc_policy.cpp"),
-           "-o", POLICY_LIB]
+           "-o", target]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"g++ failed on kvc_policy.cpp:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print("built", POLICY_LIB)
-    return POLICY_LIB
+        print("built", target)
+    return target
 
 
 if __name__ == "__main__":

@@ -9,7 +9,8 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libkvc_policy.so")
+# KVC_POLICY_LIBRARY points at another build of the same source (the sanitizer run of the tests)
+_LIB_PATH = os.environ.get("KVC_POLICY_LIBRARY") or os.path.join(_PKG, "libkvc_policy.so")
 _lib = None
 
 _i64, _f64, _i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int32
