@@ -27,7 +27,9 @@ def causal_attention_flops(S: int, q_heads: int, head_dim: int) -> float:
 
 def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int = 32, kv_heads: int = 8,
                       head_dim: int = 128, block_size: int = 16, reps: int = 5, seed: int = 0,
-                      fit_from: int = 2048) -> Dict:
+                      fit_from: int = 2048, batch: int = 1) -> Dict:
+    """Time the causal attention of `batch` requests of S tokens each (recomputed in one launch,
+    every request with a block list of its own) for every S in seq_lens."""
     import torch
 
     from . import binding as K
@@ -35,17 +37,18 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
 
     gen = torch.Generator(device="cpu").manual_seed(seed)
     smax = max(seq_lens)
-    nb = (smax + block_size - 1) // block_size + 8
+    per_seq = (smax + block_size - 1) // block_size
+    nb = per_seq * batch + 8
     k_cache = torch.randn((nb, kv_heads, block_size, head_dim), generator=gen).to(torch.bfloat16).cuda()
     v_cache = torch.randn((nb, kv_heads, block_size, head_dim), generator=gen).to(torch.bfloat16).cuda()
-    q_all = torch.randn((smax, q_heads, head_dim), generator=gen).to(torch.bfloat16).cuda()
-    table = torch.randperm(nb, generator=gen)[None, :].to(torch.int32).cuda()
+    q_all = torch.randn((smax * batch, q_heads, head_dim), generator=gen).to(torch.bfloat16).cuda()
+    table = torch.randperm(nb, generator=gen)[:per_seq * batch].reshape(batch, per_seq).to(torch.int32).cuda()
     stream = torch.cuda.current_stream()
     samples: List[Dict] = []
     for S in seq_lens:
-        q = q_all[:S].contiguous()
-        lens = torch.tensor([S], dtype=torch.int32, device="cuda")
-        qs = torch.tensor([0, S], dtype=torch.int32, device="cuda")
+        q = q_all[:S * batch].contiguous()
+        lens = torch.full((batch,), S, dtype=torch.int32, device="cuda")
+        qs = (torch.arange(batch + 1, dtype=torch.int32) * S).cuda()
         out = torch.empty_like(q)
         scale = 1.0 / math.sqrt(head_dim)
         K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
@@ -57,8 +60,8 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
         b.record(stream)
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / reps
-        fl = causal_attention_flops(S, q_heads, head_dim)
-        samples.append({"S": int(S), "layer_ms": ms, "all_layers_ms": ms * layers,
+        fl = causal_attention_flops(S, q_heads, head_dim) * batch
+        samples.append({"S": int(S), "batch": int(batch), "layer_ms": ms, "all_layers_ms": ms * layers,
                         "tflops": fl / ms / 1e9, "frac_of_mfma_peak": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS})
     fit = [s for s in samples if s["S"] >= fit_from] if sum(s["S"] >= fit_from for s in samples) >= 2 else samples
     alpha, beta, _ = policy.fit_power_law([s["S"] for s in fit], [s["all_layers_ms"] for s in fit])
@@ -71,7 +74,8 @@ def markdown(res: Dict, swap_gamma_ms: float, swap_delta_ms: float) -> str:
     from . import policy
 
     m = res["model"]
-    lines = ["| S tokens | per layer ms | all %d layers ms | TFLOP/s | %% of MFMA peak |" % m["layers"], "|---|---|---|---|---|"]
+    lines = ["%d request(s) per launch." % res["samples"][0].get("batch", 1), "",
+             "| S tokens | per layer ms | all %d layers ms | TFLOP/s | %% of MFMA peak |" % m["layers"], "|---|---|---|---|---|"]
     for s in res["samples"]:
         lines.append("| %d | %.3f | %.2f | %.1f | %.1f |" % (s["S"], s["layer_ms"], s["all_layers_ms"], s["tflops"],
                                                            100 * s["frac_of_mfma_peak"]))
@@ -90,12 +94,13 @@ def main() -> int:
     ap.add_argument("--kv-heads", type=int, default=8)
     ap.add_argument("--seq-lens", type=int, nargs="+", default=[256, 512, 1024, 2048, 4096, 8192, 16384])
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=1, help="requests of S tokens recomputed in one launch")
     ap.add_argument("--markdown", action="store_true", help="print a table instead of JSON")
     ap.add_argument("--swap-gamma-ms", type=float, default=0.004744, help="slope of the swap regressor (ms per token)")
     ap.add_argument("--swap-delta-ms", type=float, default=0.145, help="offset of the swap regressor (ms)")
     args = ap.parse_args()
     res = profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads, kv_heads=args.kv_heads,
-                            reps=args.reps)
+                            reps=args.reps, batch=args.batch)
     print(markdown(res, args.swap_gamma_ms, args.swap_delta_ms) if args.markdown else json.dumps(res))
     return 0
 
