@@ -154,6 +154,23 @@ def main() -> int:
                                                     rep["out"].data_ptr(), dref, rep["ws"].data_ptr(), ws_bytes, sh)
         assert rc == 0, K.status_string(rc)
 
+    # the same attention from a schedule built once per iteration (what the layers of a model share)
+    sched = None
+    if K.schedule_bytes(desc) > 0:
+        sched = K.attn_schedule_build(base["tables"], base["lens"], desc)
+        sched_bytes = sched.numel()
+
+    def attn_scheduled(rep):
+        rc = lib.kvc_paged_attention_decode_scheduled(rep["q"].data_ptr(), rep["k"].data_ptr(), rep["v"].data_ptr(),
+                                                      sched.data_ptr(), sched_bytes, w.scale, rep["out"].data_ptr(),
+                                                      dref, rep["ws"].data_ptr(), ws_bytes, sh)
+        assert rc == 0, K.status_string(rc)
+
+    def build_schedule(rep):
+        rc = lib.kvc_attn_schedule_build(rep["tables"].data_ptr(), rep["lens"].data_ptr(), dref, sched.data_ptr(),
+                                         sched_bytes, sh)
+        assert rc == 0, K.status_string(rc)
+
     def copy(rep):
         rc = lib.kvc_kv_block_copy(ctypes.byref(rep["src_pool"]), ctypes.byref(rep["dst_pool"]),
                                    rep["mapping"].data_ptr(), len(src_ids), sh)
@@ -240,6 +257,19 @@ def main() -> int:
     copy_region = timed_region(copy, K_, W_)
     copy_avg, copy_med, _, _ = timed_events(copy, K_, W_)
     hot_avg, hot_med, _, _ = timed_events(attn, K_, W_, hot=True)
+    sched_region = sched_build = None
+    if sched is not None:
+        sched_region = timed_region(attn_scheduled, K_, W_)
+        sched_build = timed_region(build_schedule, min(K_, 100), 10)
+        if not args.no_check:   # same bits as the stateless call on the same replica
+            attn(reps[0]); a_bits = reps[0]["out"].view(torch.int16).clone()
+            attn_scheduled(reps[0]); torch.cuda.synchronize()
+            if not torch.equal(a_bits, reps[0]["out"].view(torch.int16)):
+                print("bench.py: scheduled attention differs from the stateless call", file=sys.stderr)
+                return 4
+        log(f"[bench] attention from a prebuilt schedule {sched_region*1e6:.1f} us back-to-back "
+            f"({100.0 * attn_bytes / sched_region / 1e9 / HBM_PEAK_GBS:.1f} % of peak); building the schedule "
+            f"{sched_build*1e6:.1f} us, once per iteration")
     log(f"[bench] step {step_s*1e6:.1f} us | attention avg {attn_avg*1e6:.1f} med {attn_med*1e6:.1f} us "
         f"(hot {hot_med*1e6:.1f}) | partial kernel {part_avg*1e6:.1f} us back-to-back, {part_pair_avg*1e6:.1f} us "
         f"event pairs | attention back-to-back {attn_region*1e6:.1f} us | copy avg {copy_avg*1e6:.1f} us, "
@@ -324,6 +354,11 @@ def main() -> int:
             "attention_us_hot_same_replica": round(hot_med * 1e6, 2),
             "tokens_per_s": round(w.num_seqs / attn_avg, 1),
             "copy_us": round(copy_avg * 1e6, 2), "copy_GBs": round(copy_bytes / copy_avg / 1e9, 1),
+            "attention_pct_of_peak_back_to_back": round(100.0 * attn_bytes / attn_region / 1e9 / HBM_PEAK_GBS, 2),
+            "attention_scheduled_us_back_to_back": None if sched_region is None else round(sched_region * 1e6, 2),
+            "attention_scheduled_pct_of_peak_back_to_back":
+                None if sched_region is None else round(100.0 * attn_bytes / sched_region / 1e9 / HBM_PEAK_GBS, 2),
+            "schedule_build_us": None if sched_build is None else round(sched_build * 1e6, 2),
         },
         "roofline": {"bound": "hbm", "kernel": {1: "pa_partial_valu_kernel", 2: "pa_partial_mfma_kernel", 3: "pa_partial_mfma_kernel", 4: "pa_stream_mfma_kernel"}[int(plan.kernel)],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

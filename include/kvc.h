@@ -167,6 +167,36 @@ KVC_API int kvc_paged_attention_decode_merge(const int32_t *context_lens, void *
                                      size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same attention with the placement work taken out of the call.  Within one iteration of an
+ * iteration-level scheduler (Section 3.1) every layer of the model attends over the same
+ * block_tables and context_lens; what the balanced kernel derives from them at the start of every
+ * launch (prefix table of the batch, which tiles each wavefront takes, their pool addresses, which
+ * contexts are cut where) can therefore be computed once per iteration and reused by all layers.
+ *   kvc_attn_schedule_bytes   bytes of device memory a schedule for `desc` needs (0 when the
+ *                             descriptor is not served by the balanced kernel, or is invalid);
+ *                             a host-side bound that depends on num_seqs and max_context_len.
+ *   kvc_attn_schedule_build   one short launch that fills `schedule` (256-byte aligned device
+ *                             memory) from block_tables and context_lens.  The schedule stays valid
+ *                             until either array changes; it may be rebuilt in place.
+ *   kvc_paged_attention_decode_scheduled
+ *                             kvc_paged_attention_decode with block_tables / context_lens replaced
+ *                             by the schedule built from them (same desc): same kernel, same
+ *                             split, bit-identical output; the first KV bytes are requested after
+ *                             one memory round trip instead of three.  Workspace rules as above.
+ * Errors: KVC_ERR_UNSUPPORTED when the descriptor does not use the balanced kernel,
+ * KVC_ERR_WORKSPACE when `schedule` is NULL or smaller than kvc_attn_schedule_bytes.  A schedule
+ * built for other arrays or another descriptor is not detected: undefined behaviour.
+ */
+KVC_API size_t kvc_attn_schedule_bytes(const kvc_attn_desc *desc);
+KVC_API int kvc_attn_schedule_build(const int32_t *block_tables, const int32_t *context_lens,
+                                    const kvc_attn_desc *desc, void *schedule, size_t schedule_bytes,
+                                    void *hip_stream);
+KVC_API int kvc_paged_attention_decode_scheduled(const void *q, const void *k_cache, const void *v_cache,
+                                                 const void *schedule, size_t schedule_bytes, float scale,
+                                                 void *out, const kvc_attn_desc *desc, void *workspace,
+                                                 size_t workspace_bytes, void *hip_stream);
+
+/*
  * kvc_paged_attention_decode for callers that cannot allocate device memory or hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, checks, kernels and results as kvc_paged_attention_decode, but

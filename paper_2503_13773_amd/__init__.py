@@ -12,7 +12,8 @@ from .binding import (  # noqa: F401
     KVC_F32, KVC_BF16, KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_LDS, KERNEL_MFMA_BALANCED,
     KvcError, AttnDesc, AttnPlan, Pool, lib, library_path, attn_desc, attn_plan,
     workspace_bytes, workspace_init, new_workspace, paged_attention_decode, paged_attention_decode_partial,
-    paged_attention_decode_noalloc, NOALLOC_WORKSPACE_BYTES,
+    paged_attention_decode_noalloc, NOALLOC_WORKSPACE_BYTES, schedule_bytes, attn_schedule_build,
+    paged_attention_decode_scheduled,
     paged_attention_decode_merge, paged_attention_prefill, validate_attention_inputs, kv_block_copy, kv_cache_append,
     validate_block_mapping, pool_of, status_string, version,
 )

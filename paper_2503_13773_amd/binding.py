@@ -73,6 +73,12 @@ def lib():
         fn.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp, sz, vp]
     L.kvc_paged_attention_decode_workspace_init.restype = ctypes.c_int
     L.kvc_paged_attention_decode_workspace_init.argtypes = [vp, sz, vp]
+    L.kvc_attn_schedule_bytes.restype = sz
+    L.kvc_attn_schedule_bytes.argtypes = [dp]
+    L.kvc_attn_schedule_build.restype = ctypes.c_int
+    L.kvc_attn_schedule_build.argtypes = [i32p, i32p, dp, vp, sz, vp]
+    L.kvc_paged_attention_decode_scheduled.restype = ctypes.c_int
+    L.kvc_paged_attention_decode_scheduled.argtypes = [vp, vp, vp, vp, sz, f, vp, dp, vp, sz, vp]
     L.kvc_paged_attention_decode_noalloc.restype = ctypes.c_int
     L.kvc_paged_attention_decode_noalloc.argtypes = [vp, vp, vp, i32p, i32p, f, vp, dp, vp]
     L.kvc_paged_attention_decode_merge.restype = ctypes.c_int
@@ -197,6 +203,33 @@ def paged_attention_decode(q, k_cache, v_cache, block_tables, context_lens, scal
         q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
         context_lens.data_ptr(), float(scale), out.data_ptr(), ctypes.byref(desc), ws_ptr, ws_len,
         _stream_handle(stream)), "kvc_paged_attention_decode")
+    return out
+
+
+def schedule_bytes(desc: AttnDesc) -> int:
+    return int(lib().kvc_attn_schedule_bytes(ctypes.byref(desc)))
+
+
+def attn_schedule_build(block_tables, context_lens, desc: AttnDesc, schedule=None, stream=None):
+    """Placement of the balanced kernel's workers for (block_tables, context_lens): built once per
+    iteration, reused by every layer's paged_attention_decode_scheduled.  Returns the schedule tensor."""
+    need = schedule_bytes(desc)
+    if schedule is None:
+        schedule = torch.empty(max(need, 256), dtype=torch.uint8, device=block_tables.device)
+    _check(lib().kvc_attn_schedule_build(block_tables.data_ptr(), context_lens.data_ptr(), ctypes.byref(desc),
+                                         schedule.data_ptr(), schedule.numel(), _stream_handle(stream)),
+           "kvc_attn_schedule_build")
+    return schedule
+
+
+def paged_attention_decode_scheduled(q, k_cache, v_cache, schedule, scale: float, out, desc: AttnDesc,
+                                     workspace, stream=None):
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib().kvc_paged_attention_decode_scheduled(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), schedule.data_ptr(), schedule.numel(), float(scale),
+        out.data_ptr(), ctypes.byref(desc), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _stream_handle(stream)), "kvc_paged_attention_decode_scheduled")
     return out
 
 

@@ -211,7 +211,7 @@ int run_partial(const void *q, const void *k_cache, const void *v_cache, const i
                                      desc->dtype, desc->head_dim, int(pl.partial_grid), stream);
     else if (pl.kernel == KVC_KERNEL_MFMA_BALANCED)
         e = kvc::launch_partial_mfma_stream(q, k_cache, v_cache, block_tables, context_lens, out,
-                                            ws, p, int(pl.partial_grid), stream);
+                                            ws, p, int(pl.partial_grid), 0, kvc::Schedule{}, stream);
     else
         e = kvc::launch_partial_mfma(q, k_cache, v_cache, block_tables, context_lens, out, ws, p,
                                      int(pl.partial_grid), stream);
@@ -225,6 +225,42 @@ int run_merge(const int32_t *context_lens, void *out, const kvc_attn_desc *desc,
     const hipError_t e = kvc::launch_merge(context_lens, out, ws, p, desc->dtype, desc->head_dim,
                                            pl.kernel != KVC_KERNEL_VALU, int(pl.merge_grid), stream);
     return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
+// Layout of a schedule buffer for a descriptor served by the balanced kernel.
+struct ScheduleLayout {
+    uint64_t pref_off, ctx_off, plans_off, tiles_off, bytes;
+    int stride;
+};
+
+bool schedule_layout(const kvc_attn_desc &d, const Plan &pl, ScheduleLayout *L) {
+    if (pl.kernel != KVC_KERNEL_MFMA_BALANCED) return false;
+    const int64_t workers = int64_t(kvc::kNumCUs) * kvc::kWaves;
+    const int64_t units_per_tile = d.block_size >= 16 ? 1 : 16 / d.block_size;
+    // no worker takes more flat units than this, whatever the context lengths turn out to be
+    const int64_t max_units = int64_t(d.num_seqs) * d.num_kv_heads * (ceil_div(pl.max_context_len, 16) + 1);
+    const int64_t chunk = std::max<int64_t>(pl.min_chunk_tiles, ceil_div(max_units, workers));
+    const int64_t stride = chunk * units_per_tile;
+    if (stride > (int64_t(1) << 28)) return false;
+    auto up = [](uint64_t x) { return (x + 255) & ~uint64_t(255); };
+    L->stride = int(stride);
+    L->pref_off = 0;
+    L->ctx_off = up(uint64_t(d.num_seqs + 2) * 4);
+    L->plans_off = L->ctx_off + up(uint64_t(d.num_seqs) * 4);
+    L->tiles_off = L->plans_off + up(uint64_t(workers) * 16 * 4);
+    L->bytes = L->tiles_off + up(uint64_t(workers) * uint64_t(stride) * 4);
+    return true;
+}
+
+kvc::Schedule schedule_view(void *base, const ScheduleLayout &L) {
+    auto *b = static_cast<unsigned char *>(base);
+    kvc::Schedule s;
+    s.pref = reinterpret_cast<int *>(b + L.pref_off);
+    s.ctx = reinterpret_cast<int *>(b + L.ctx_off);
+    s.plans = reinterpret_cast<int *>(b + L.plans_off);
+    s.tiles = reinterpret_cast<int *>(b + L.tiles_off);
+    s.stride = L.stride;
+    return s;
 }
 
 int check_attn_args(const void *q, const void *k_cache, const void *v_cache,
@@ -385,6 +421,59 @@ int kvc_paged_attention_decode_noalloc(const void *q, const void *k_cache, const
     rc = run_partial(q, k_cache, v_cache, block_tables, context_lens, scale, out, desc, pl, ws, stream);
     if (rc != KVC_OK) return rc;
     return run_merge(context_lens, out, desc, pl, ws, stream);
+}
+
+size_t kvc_attn_schedule_bytes(const kvc_attn_desc *desc) {
+    Plan pl;
+    ScheduleLayout L;
+    if (make_plan(desc, &pl) != KVC_OK || !schedule_layout(*desc, pl, &L)) return 0;
+    return size_t(L.bytes);
+}
+
+int kvc_attn_schedule_build(const int32_t *block_tables, const int32_t *context_lens,
+                            const kvc_attn_desc *desc, void *schedule, size_t schedule_bytes,
+                            void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    ScheduleLayout L;
+    if (!schedule_layout(*desc, pl, &L)) return KVC_ERR_UNSUPPORTED;
+    if (!schedule || schedule_bytes < L.bytes) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(schedule) & 255u) return KVC_ERR_ALIGN;
+    if (desc->num_seqs == 0) return KVC_OK;
+    if (!block_tables || !context_lens) return KVC_ERR_NULL;
+    const kvc::AttnParams p = make_params(*desc, pl, 1.0f);
+    const hipError_t e = kvc::launch_partial_mfma_stream(nullptr, nullptr, nullptr, block_tables, context_lens,
+                                                         nullptr, kvc::Workspace{}, p, int(pl.partial_grid), 1,
+                                                         schedule_view(schedule, L),
+                                                         static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
+}
+
+int kvc_paged_attention_decode_scheduled(const void *q, const void *k_cache, const void *v_cache,
+                                         const void *schedule, size_t schedule_bytes, float scale,
+                                         void *out, const kvc_attn_desc *desc, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream) {
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != KVC_OK) return rc;
+    ScheduleLayout L;
+    if (!schedule_layout(*desc, pl, &L)) return KVC_ERR_UNSUPPORTED;
+    if (!schedule || schedule_bytes < L.bytes) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(schedule) & 255u) return KVC_ERR_ALIGN;
+    if (desc->num_seqs == 0) return KVC_OK;
+    if (!q || !k_cache || !v_cache || !out) return KVC_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return KVC_ERR_ALIGN;
+    if (!isfinite(scale)) return KVC_ERR_BAD_SHAPE;
+    kvc::Workspace ws;
+    rc = check_workspace(pl, workspace, workspace_bytes, &ws);
+    if (rc != KVC_OK) return rc;
+    const kvc::AttnParams p = make_params(*desc, pl, scale);
+    const hipError_t e = kvc::launch_partial_mfma_stream(q, k_cache, v_cache, nullptr, nullptr, out, ws, p,
+                                                         int(pl.partial_grid), 2,
+                                                         schedule_view(const_cast<void *>(schedule), L),
+                                                         static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVC_OK : hip_failed(e);
 }
 
 int kvc_validate_attention_inputs(const int32_t *block_tables, const int32_t *context_lens,

@@ -54,6 +54,17 @@ struct Workspace {
 };
 constexpr size_t kWorkspaceHeaderBytes = 4096;
 
+// Placement of the balanced kernel's workers for one (block_tables, context_lens), kept in device
+// memory between a build launch and the attention launches of the layers that share it:
+// pref [num_seqs + 2], ctx [num_seqs], plans [workers][16], tiles [workers][stride] (all int32).
+struct Schedule {
+    int *pref;
+    int *ctx;
+    int *plans;
+    int *tiles;
+    int stride;  // tile-address entries a worker's share of `tiles` holds
+};
+
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup, every attention kernel
 constexpr int kWaves = kThreads / 64;
 constexpr int kNumCUs = 256;        // MI355X
@@ -68,10 +79,12 @@ hipError_t launch_partial_valu(const void *q, const void *k_cache, const void *v
 hipError_t launch_partial_mfma(const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens, void *out,
                                Workspace ws, const AttnParams &p, int grid, hipStream_t stream);
+// mode 0: stateless call; 1: only build `sched` from block_tables / context_lens; 2: run from `sched`
+// (block_tables / context_lens unused).
 hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const void *v_cache,
                                       const int32_t *block_tables, const int32_t *context_lens,
                                       void *out, Workspace ws, const AttnParams &p, int grid,
-                                      hipStream_t stream);
+                                      int mode, Schedule sched, hipStream_t stream);
 // base2: partials are in base-2 units.
 hipError_t launch_merge(const int32_t *context_lens, void *out, Workspace ws, const AttnParams &p,
                         int dtype, int head_dim, bool base2, int grid, hipStream_t stream);

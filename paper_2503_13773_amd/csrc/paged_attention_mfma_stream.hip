@@ -265,14 +265,24 @@ struct RowCursor {
     int tiles;   // t_n (the row spans t_n + kRowCost flat units)
 };
 
+// What a launch does with the placement of the workers (the start-up work that depends only on
+// block_tables and context_lens, which all layers of one decode step share):
+//   kDirect     computes it and streams (the stateless call);
+//   kBuild      computes it and writes it to a schedule buffer, nothing else;
+//   kScheduled  reads it from a schedule buffer and streams: the prefix table, the worker's plan
+//               and its first tile addresses arrive in one memory round trip instead of the
+//               three dependent ones (context lengths, block table, first tile) of kDirect.
+enum : int { kDirect = 0, kBuild = 1, kScheduled = 2 };
+constexpr int kPlanInts = 16;  // a worker's plan in the schedule buffer
+
 // MAXSPT: sequences per thread in the start-up prefix sum (batches up to MAXSPT * 256 sequences);
 // the small instance keeps the start-up of ordinary batches short.
-template <int MAXSPT>
+template <int MAXSPT, int MODE>
 __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, uint16_t *__restrict__ out, Workspace ws,
-    AttnParams p, int unit_log2, int units_per_block_log2) {
+    AttnParams p, int unit_log2, int units_per_block_log2, Schedule sched) {
     constexpr int kSeqs = MAXSPT * kThreads;
     __shared__ int s_pref[kSeqs + 2];  // exclusive prefix of flat units (tiles + row cost) per sequence (+ guard)
     __shared__ int s_ctx[kSeqs];       // context length per sequence
@@ -284,6 +294,21 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     const int quad = lane >> 4, r = lane & 15;
     const int nseq = p.num_seqs;
 
+    const int worker = blockIdx.x * kWaves + wave;
+    const int U_log2 = 4 - unit_log2;                 // log2(units per tile)
+    int plan_word = 0;                                // kScheduled: lane i < kPlanInts holds word i of the plan
+    if constexpr (MODE == kScheduled) {
+        // one round trip: the worker's plan, its first tile addresses (as many as the staging
+        // window or its share of the schedule holds; entries past its tiles are never used) and
+        // the prefix table of the batch
+        if (lane < kPlanInts) plan_word = sched.plans[size_t(worker) * kPlanInts + lane];
+        const int *mine = sched.tiles + size_t(worker) * sched.stride;
+        const int window = min(kStageTiles << U_log2, sched.stride);
+        for (int e = lane; e < window; e += 64) s_tile[wave][e] = mine[e];
+        for (int n = tid; n < nseq + 2; n += kThreads) s_pref[n] = sched.pref[n];
+        for (int n = tid; n < nseq; n += kThreads) s_ctx[n] = sched.ctx[n];
+        __syncthreads();
+    } else
     // ---- prefix sum of 16-token tiles per sequence (thread t owns sequences t*spt .. +spt-1)
     {
         constexpr int kMaxSpt = MAXSPT;
@@ -325,21 +350,34 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         __syncthreads();
     }
 
-    // empty contexts give rows of zeros; workgroup b looks after sequences b, b + grid, ...
-    for (int n = blockIdx.x; n < nseq; n += gridDim.x) {
-        if (s_ctx[n] == 0) {
-            uint4 *row = reinterpret_cast<uint4 *>(out + size_t(n) * p.num_q_heads * D);
-            for (int i = tid; i < p.num_q_heads * (D / 8); i += kThreads) row[i] = uint4{0u, 0u, 0u, 0u};
+    if constexpr (MODE == kBuild) {
+        if (blockIdx.x == 0) {  // every workgroup has the same table: one of them keeps it
+            for (int n = tid; n < nseq + 2; n += kThreads) sched.pref[n] = s_pref[n];
+            for (int n = tid; n < nseq; n += kThreads) sched.ctx[n] = s_ctx[n];
+        }
+    } else {
+        // empty contexts give rows of zeros; workgroup b looks after sequences b, b + grid, ...
+        for (int n = blockIdx.x; n < nseq; n += gridDim.x) {
+            if (s_ctx[n] == 0) {
+                uint4 *row = reinterpret_cast<uint4 *>(out + size_t(n) * p.num_q_heads * D);
+                for (int i = tid; i < p.num_q_heads * (D / 8); i += kThreads) row[i] = uint4{0u, 0u, 0u, 0u};
+            }
         }
     }
 
     const int Hkv = p.num_kv_heads;
     const int G = p.group;
+    // the plan of a worker with nothing to do
+    auto write_empty_plan = [&]() __attribute__((always_inline)) {
+        if (MODE == kBuild && lane < kPlanInts) sched.plans[size_t(worker) * kPlanInts + lane] = 0;
+    };
     const int T = uniform(s_pref[nseq]) * Hkv;
     const int workers = gridDim.x * kWaves;
     const int C = max(p.min_chunk_tiles, (T + workers - 1) / workers);
-    const int worker = blockIdx.x * kWaves + wave;
-    if (int64_t(worker) * C >= T) return;
+    if (MODE != kScheduled && int64_t(worker) * C >= T) {
+        write_empty_plan();
+        return;
+    }
     const int f0 = worker * C;
     const int f1 = min(T, f0 + C);       // the worker's flat units are [f0, f1)
 
@@ -366,7 +404,22 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     // ---- place the worker: largest n with s_pref[n] * Hkv <= f0 (that sequence is not empty)
     RowCursor first;
     int first_tile;
-    {
+    int NT = 0;
+    // Cut rows this worker holds a piece of (at most one through slot H: its first segment, when
+    // that starts past the row's tile 0; at most one through slot T: its last segment, when that
+    // starts at tile 0 and stops before the row's end): sequence, KV head, first worker of the
+    // row, number of workers on the row (0 = none).  Known from the worker's placement alone, so
+    // that it can announce its arrival before its last tiles are consumed.
+    int h_n = 0, h_kvh = 0, h_j0 = 0, h_cnt = 0;
+    int t_n = 0, t_kvh = 0, t_j0 = 0, t_cnt = 0;
+    if constexpr (MODE == kScheduled) {
+        auto word = [&](int i) { return __builtin_amdgcn_readlane(plan_word, i); };
+        NT = word(0);
+        first.n = word(1); first.kvh = word(2); first.pref = word(3); first.tiles = word(4);
+        first_tile = word(5);
+        h_n = word(6); h_kvh = word(7); h_j0 = word(8); h_cnt = word(9);
+        t_n = word(10); t_kvh = word(11); t_j0 = word(12); t_cnt = word(13);
+    } else {
         int lo = 0, hi = nseq;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
@@ -385,10 +438,9 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     }
     // tiles of this worker: the part of [f0, f1) that falls on tiles rather than cost units;
     // the walk also finds the last row it touches and where its piece of that row ends
-    int NT = 0;
-    RowCursor last = first;
-    int last_t0 = first_tile, last_end = first_tile;
-    {
+    if constexpr (MODE != kScheduled) {
+        RowCursor last = first;
+        int last_t0 = first_tile, last_end = first_tile;
         RowCursor c = first;
         int t0 = first_tile;
         while (c.n < nseq) {
@@ -401,8 +453,29 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             c = next_row(c);
             t0 = 0;
         }
+        if (first_tile > 0) {
+            const int row_f = first.pref * Hkv + first.kvh * (first.tiles + kRowCost);
+            h_n = first.n; h_kvh = first.kvh; h_j0 = row_f / C;
+            h_cnt = (row_f + first.tiles - 1) / C - h_j0 + 1;
+        }
+        if (NT > 0 && last_t0 == 0 && last_end < last.tiles) {
+            const int row_f = last.pref * Hkv + last.kvh * (last.tiles + kRowCost);
+            t_n = last.n; t_kvh = last.kvh; t_j0 = row_f / C;
+            t_cnt = (row_f + last.tiles - 1) / C - t_j0 + 1;
+        }
     }
-    if (NT == 0) return;  // the range covered cost units only; no row counts this worker
+    if (NT == 0) {  // the range covered cost units only; no row counts this worker
+        write_empty_plan();
+        return;
+    }
+    if constexpr (MODE == kBuild) {
+        const int words[kPlanInts] = {NT, first.n, first.kvh, first.pref, first.tiles, first_tile, h_n, h_kvh,
+                                      h_j0, h_cnt, t_n, t_kvh, t_j0, t_cnt, 0, 0};
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < kPlanInts; ++i) mine = lane == i ? words[i] : mine;
+        if (lane < kPlanInts) sched.plans[size_t(worker) * kPlanInts + lane] = mine;
+    }
 
     // ---- tile addresses of the worker's range, staged in LDS
     // A "unit" is the part of a 16-token tile that lies in one block: min(block_size, 16)
@@ -413,7 +486,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     // last valid unit: they are loaded and masked, never taken from the block table.
     // Staging the addresses up front keeps the steady-state loop free of dependent
     // block-table loads: the issue side needs two LDS reads per tile and no row bookkeeping.
-    const int U_log2 = 4 - unit_log2;                 // log2(units per tile)
     const int unit_tokens = 1 << unit_log2;
     const int upb_mask = (1 << units_per_block_log2) - 1;
     RowCursor rf = first;           // fill cursor
@@ -421,6 +493,12 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     int staged_base = 0;            // worker-relative index of the first staged tile
     auto stage_tiles = [&](int from) __attribute__((always_inline)) {
         const int count = min(kStageTiles, NT - from);
+        if constexpr (MODE == kScheduled) {  // copied from the schedule
+            const int *mine = sched.tiles + size_t(worker) * sched.stride + (size_t(from) << U_log2);
+            for (int e = lane; e < (count << U_log2); e += 64) s_tile[wave][e] = mine[e];
+            staged_base = from;
+            return;
+        }
         int off = 0;
         while (off < count) {
             if (tf == rf.tiles) {
@@ -442,7 +520,17 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         }
         staged_base = from;
     };
-    stage_tiles(0);
+    if constexpr (MODE == kBuild) {
+        // every tile address of the worker, window by window, into its share of the schedule
+        int *mine = sched.tiles + size_t(worker) * sched.stride;
+        for (int from = 0; from < NT; from += kStageTiles) {
+            stage_tiles(from);
+            const int count = min(kStageTiles, NT - from);
+            for (int e = lane; e < (count << U_log2); e += 64) mine[(size_t(from) << U_log2) + e] = s_tile[wave][e];
+        }
+        return;
+    }
+    if constexpr (MODE == kDirect) stage_tiles(0);  // kScheduled: the first window came with the plan
 
     // Per-lane constants of the tile loads: K wants token r, V wants tokens 4*quad + i.
     const size_t unit_elems = size_t(unit_tokens) * D;
@@ -475,24 +563,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     HeadState st;
     st.reset();
 
-    // Cut rows this worker holds a piece of (at most one through slot H: its first segment, when
-    // that starts past the row's tile 0; at most one through slot T: its last segment, when that
-    // starts at tile 0 and stops before the row's end): sequence, KV head, first worker of the
-    // row, number of workers on the row (0 = none).  Known from the worker's placement alone, so
-    // that it can announce its arrival before its last tiles are consumed.  The H partial is
-    // parked in `hp` until the worker's end; the T partial is still in `st` then.
-    int h_n = 0, h_kvh = 0, h_j0 = 0, h_cnt = 0;
-    int t_n = 0, t_kvh = 0, t_j0 = 0, t_cnt = 0;
-    if (first_tile > 0) {
-        const int row_f = first.pref * Hkv + first.kvh * (first.tiles + kRowCost);
-        h_n = first.n; h_kvh = first.kvh; h_j0 = row_f / C;
-        h_cnt = (row_f + first.tiles - 1) / C - h_j0 + 1;
-    }
-    if (last_t0 == 0 && last_end < last.tiles) {
-        const int row_f = last.pref * Hkv + last.kvh * (last.tiles + kRowCost);
-        t_n = last.n; t_kvh = last.kvh; t_j0 = row_f / C;
-        t_cnt = (row_f + last.tiles - 1) / C - t_j0 + 1;
-    }
+    // The H partial is parked in `hp` until the worker's end; the T partial is still in `st` then.
     HeadState hp;
     hp.reset();
 
@@ -654,7 +725,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
 hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const void *v_cache,
                                       const int32_t *block_tables, const int32_t *context_lens,
                                       void *out, Workspace ws, const AttnParams &p, int grid,
-                                      hipStream_t stream) {
+                                      int mode, Schedule sched, hipStream_t stream) {
     // unit = min(block_size, 16) tokens; blocks hold block_size / unit units
     int unit_log2 = 4, upb_log2 = 0;
     if (p.block_size < 16) {
@@ -662,16 +733,23 @@ hipError_t launch_partial_mfma_stream(const void *q, const void *k_cache, const 
     } else {
         while ((16 << upb_log2) < p.block_size) ++upb_log2;
     }
-    if (p.num_seqs <= 4 * kThreads)
-        pa_stream_mfma_kernel<4><<<dim3(grid), dim3(kThreads), 0, stream>>>(
-            static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
-            static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
-            static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
-    else
-        pa_stream_mfma_kernel<kMaxStreamSeqs / kThreads><<<dim3(grid), dim3(kThreads), 0, stream>>>(
-            static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
-            static_cast<const uint16_t *>(v_cache), block_tables, context_lens,
-            static_cast<uint16_t *>(out), ws, p, unit_log2, upb_log2);
+    const auto *q_ = static_cast<const uint16_t *>(q), *k_ = static_cast<const uint16_t *>(k_cache),
+               *v_ = static_cast<const uint16_t *>(v_cache);
+    auto *o_ = static_cast<uint16_t *>(out);
+    const dim3 g(grid), b(kThreads);
+    constexpr int kBig = kMaxStreamSeqs / kThreads;
+    const bool small = p.num_seqs <= 4 * kThreads;
+#define KVC_LAUNCH_STREAM(SPT, MODE) \
+    pa_stream_mfma_kernel<SPT, MODE><<<g, b, 0, stream>>>(q_, k_, v_, block_tables, context_lens, o_, ws, p, \
+                                                          unit_log2, upb_log2, sched)
+    if (mode == kDirect) {
+        if (small) KVC_LAUNCH_STREAM(4, kDirect); else KVC_LAUNCH_STREAM(kBig, kDirect);
+    } else if (mode == kBuild) {
+        if (small) KVC_LAUNCH_STREAM(4, kBuild); else KVC_LAUNCH_STREAM(kBig, kBuild);
+    } else {
+        if (small) KVC_LAUNCH_STREAM(4, kScheduled); else KVC_LAUNCH_STREAM(kBig, kScheduled);
+    }
+#undef KVC_LAUNCH_STREAM
     return hipGetLastError();
 }
 

@@ -405,3 +405,67 @@ def test_large_batches_of_short_sequences(oracle_mod, nseq):
     plan = K.attn_plan(K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=80))
     assert plan.kernel == (BALANCED if nseq <= 4096 else MFMA)
     check(w, oracle_mod, f"{nseq} short sequences")
+
+
+# ---------------------------------------------------------------------------
+# schedule built once per iteration, reused by the layers
+# ---------------------------------------------------------------------------
+def _scheduled_equals_direct(w, oracle_mod, label, **opts):
+    import paper_2503_13773_amd as K
+    d = to_device(w)
+    desc = K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=max(1, w.max_context_len), kernel=BALANCED, **opts)
+    assert K.schedule_bytes(desc) > 0
+    print(f"[case] scheduled {label} {w.name} nseq={w.num_seqs} opts={opts} schedule {K.schedule_bytes(desc)} B", flush=True)
+    ws = K.new_workspace(desc)
+    direct = K.paged_attention_decode(d["q"], d["k"], d["v"], d["tables"], d["lens"], w.scale, desc=desc, workspace=ws)
+    sched = K.attn_schedule_build(d["tables"], d["lens"], desc)
+    # the block table and the lengths are not read by the scheduled call: poison them
+    d["tables"].fill_(-7)
+    d["lens"].fill_(-7)
+    outs = []
+    for layer in range(3):                      # "layers": the same schedule, other q each time would do as well
+        outs.append(K.paged_attention_decode_scheduled(d["q"], d["k"], d["v"], sched, w.scale, None, desc, ws))
+    torch.cuda.synchronize()
+    for o in outs:
+        assert np.array_equal(out_bits(o), out_bits(direct)), label
+    ref = oracle_mod.attention_of_workload(w, num_threads=8)
+    assert np.abs(out_to_f64(outs[-1]) - ref).max() <= tol_of(w)
+    assert int(ws[:4096].max()) == 0
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3b", "cfg4", "cfg5"])
+def test_scheduled_call_equals_the_direct_call_full_size(oracle_mod, name):
+    _scheduled_equals_direct(W.make_config(name), oracle_mod, "full")
+
+
+def test_scheduled_call_on_ragged_empty_and_small_block_batches(oracle_mod):
+    lens = [0, 0, 5, 16, 17, 0, 33, 1, 250, 0, 0, 47, 48, 49, 700, 3, 0, 90, 16, 0]
+    for hkv in (1, 2):
+        w = custom(620 + hkv, dtype=W.BF16, lens=lens, hq=2 * hkv, hkv=hkv, d=128, bs=16)
+        w.block_tables[np.asarray(lens) == 0, :] = -1
+        for chunk in (16, 48, 1024):
+            _scheduled_equals_direct(w, oracle_mod, f"ragged chunk={chunk}", partition_tokens=chunk)
+    for bs in (4, 8, 32):
+        w = custom(630 + bs, dtype=W.BF16, lens=[1, 3, 9, 17, 100, 257, 1000], hq=8, hkv=2, d=128, bs=bs)
+        _scheduled_equals_direct(w, oracle_mod, f"bs={bs}")
+    w = custom(640, dtype=W.BF16, lens=[20000, 37, 9000], hq=2, hkv=1, d=128, bs=16)   # windows refilled from the schedule
+    _scheduled_equals_direct(w, oracle_mod, "long ranges", partition_tokens=8192)
+    w = custom(641, dtype=W.BF16, lens=[0, 0, 0], hq=4, hkv=2, d=128, bs=16)
+    _scheduled_equals_direct(w, oracle_mod, "all empty")
+
+
+def test_schedule_calls_refuse_what_they_cannot_serve():
+    import ctypes
+    import paper_2503_13773_amd as K
+    w = W.make_config("cfg3", num_seqs=4, ctx_scale=0.3)
+    d = to_device(w)
+    valu = K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=w.max_context_len, kernel=VALU)
+    assert K.schedule_bytes(valu) == 0
+    buf = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    L = K.lib()
+    assert L.kvc_attn_schedule_build(d["tables"].data_ptr(), d["lens"].data_ptr(), ctypes.byref(valu),
+                                     buf.data_ptr(), buf.numel(), None) == -4
+    ok = K.attn_desc(d["q"], d["k"], d["tables"], max_context_len=w.max_context_len)
+    assert L.kvc_attn_schedule_build(d["tables"].data_ptr(), d["lens"].data_ptr(), ctypes.byref(ok),
+                                     buf.data_ptr(), 16, None) == -5
+    assert L.kvc_attn_schedule_build(None, d["lens"].data_ptr(), ctypes.byref(ok), buf.data_ptr(), buf.numel(), None) == -1
