@@ -256,10 +256,11 @@ KVC_API int kvc_paged_attention_prefill(const void *q, const void *k_cache, cons
  *   k_new, v_new   T [num_seqs][num_kv_heads][head_dim]   (device, 16-byte aligned)
  *   positions      int32 [num_seqs] (device): token index to write for each sequence; the
  *                  token goes to block block_tables[n][pos / block_size], slot pos % block_size.
- *                  A negative position skips the sequence.
+ *                  A negative position skips the sequence, and so does one at or past
+ *                  max_blocks_per_seq * block_size (the table has no entry for it).
  * Every other byte of the caches is left untouched.  Uses desc->num_seqs, num_kv_heads,
  * head_dim, block_size, max_blocks_per_seq and dtype (the attention-only fields are ignored
- * but must be valid).  Positions and block ids are not range-checked.
+ * but must be valid).  Block ids are not range-checked.
  */
 KVC_API int kvc_kv_cache_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                                 const int32_t *block_tables, const int32_t *positions,

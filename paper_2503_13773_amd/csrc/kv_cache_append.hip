@@ -25,7 +25,9 @@ __global__ __launch_bounds__(kThreads) void kv_cache_append_kernel(
     const int h = int((gid / words_per_row) % num_kv_heads);
     const int n = int(gid / (int64_t(words_per_row) * num_kv_heads));
     const int pos = positions[n];
-    if (pos < 0) return;
+    // negative: skip the sequence; past the block table's reach: nothing to write to (not an error
+    // this launch can report, but never an out-of-range table read)
+    if (pos < 0 || (pos >> block_size_log2) >= max_blocks_per_seq) return;
     const int blk = block_tables[int64_t(n) * max_blocks_per_seq + (pos >> block_size_log2)];
     const int slot = pos & ((1 << block_size_log2) - 1);
     // cache row index: ((blk * Hkv + h) * Bs + slot), in units of words_per_row

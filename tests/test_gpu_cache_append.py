@@ -74,3 +74,27 @@ def test_chained_decode_steps_append_then_attend(oracle_mod):
                                                 dtype="bf16", num_threads=8)
         assert np.abs(out_to_f64(out) - ref).max() <= BF16_TOL, step
     assert np.array_equal(cache_bits(dk), hk.view(np.int16))
+
+
+def test_positions_past_the_block_table_are_skipped():
+    """A position at or beyond max_blocks_per_seq * block_size has no table entry: the sequence is
+    skipped like one with a negative position, nothing outside the table is read, nothing written."""
+    import paper_2503_13773_amd as K
+    rng = np.random.default_rng(77)
+    nseq, hkv, d, bs, lmax = 5, 2, 128, 16, 4
+    w = W.build_workload("append-oob", rng, dtype=W.BF16, context_lens=np.full(nseq, 20, dtype=np.int32),
+                         num_q_heads=hkv, num_kv_heads=hkv, head_dim=d, block_size=bs, max_blocks_per_seq=lmax,
+                         num_pool_blocks=None, occupancy=0.8)
+    k_new = W.f32_to_bf16_bits(rng.standard_normal((nseq, hkv, d)).astype(np.float32))
+    v_new = W.f32_to_bf16_bits(rng.standard_normal((nseq, hkv, d)).astype(np.float32))
+    pos = np.array([19, lmax * bs, lmax * bs + 5, 2 ** 30, 3], dtype=np.int32)
+    host_pos = np.where(pos >= lmax * bs, -1, pos).astype(np.int32)          # what the oracle is asked to do
+    wk, wv = w.k_cache.copy(), w.v_cache.copy()
+    oracle_mod_pos = host_pos
+    import oracle
+    oracle.kv_cache_append(k_new, v_new, wk, wv, w.block_tables, oracle_mod_pos)
+    dk, dv = dev_tensor(w.k_cache, W.BF16), dev_tensor(w.v_cache, W.BF16)
+    K.kv_cache_append(dev_tensor(k_new, W.BF16), dev_tensor(v_new, W.BF16), dk, dv,
+                      torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(pos).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(cache_bits(dk), wk.view(np.int16)) and np.array_equal(cache_bits(dv), wv.view(np.int16))
