@@ -239,9 +239,11 @@ KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int
  *                 the launch grid; rows of sequences with Qn > max_query_len beyond it are not
  *                 computed).
  * Every shape the descriptor allows is served: bf16 with head_dim 128 and group <= 16 runs on
- * the matrix cores (any block size), everything else (fp32, head_dim 64, larger groups) on the
- * vector ALUs, one workgroup per query row and head chunk.  No workspace.  desc->max_context_len,
- * partition_tokens and kernel are ignored (must be valid).
+ * the matrix cores (any block size): on 32x32 tiles when the group size is even and the scale
+ * positive, on 16x16 tiles otherwise or when desc->kernel is KVC_KERNEL_MFMA; everything else
+ * (fp32, head_dim 64, larger groups) on the vector ALUs, one workgroup per query row and head
+ * chunk.  No workspace.  desc->max_context_len and partition_tokens are ignored; desc->kernel must
+ * be valid for the shape and is otherwise ignored.
  */
 KVC_API int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *v_cache,
                                         const int32_t *block_tables, const int32_t *context_lens,

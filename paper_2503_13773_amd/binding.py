@@ -277,9 +277,10 @@ def validate_attention_inputs(block_tables, context_lens, desc: AttnDesc, stream
 
 
 def paged_attention_prefill(q, k_cache, v_cache, block_tables, context_lens, q_start, scale: float,
-                            max_query_len: int, out=None, stream=None):
+                            max_query_len: int, out=None, stream=None, kernel: int = KERNEL_AUTO):
     """Causal attention of the last Qn = q_start[n+1]-q_start[n] positions of every sequence
-    (q is [total_q][Hq][D], rows of all sequences back to back) over its block list."""
+    (q is [total_q][Hq][D], rows of all sequences back to back) over its block list.
+    kernel=KERNEL_MFMA asks for the 16x16-tile matrix-core kernel where AUTO would take 32x32 tiles."""
     for t in (q, k_cache, v_cache, block_tables, context_lens, q_start):
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError("tensors must be contiguous device tensors")
@@ -297,7 +298,7 @@ def paged_attention_prefill(q, k_cache, v_cache, block_tables, context_lens, q_s
         out = torch.empty_like(q)
     desc = AttnDesc(num_seqs=context_lens.shape[0], num_q_heads=hq, num_kv_heads=hkv, head_dim=d,
                     block_size=bs, max_blocks_per_seq=block_tables.shape[1], num_pool_blocks=nb,
-                    dtype=_dtype_code(q), max_context_len=0, partition_tokens=0, kernel=KERNEL_AUTO,
+                    dtype=_dtype_code(q), max_context_len=0, partition_tokens=0, kernel=int(kernel),
                     reserved=0)
     _check(lib().kvc_paged_attention_prefill(
         q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),

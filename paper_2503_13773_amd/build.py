@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvc_hip.so")
 SOURCES = ["kvc_api.hip", "kv_block_copy.hip", "kv_cache_append.hip", "paged_attention_valu.hip",
-           "paged_attention_mfma.hip", "paged_attention_mfma_stream.hip", "paged_attention_prefill.hip",
+           "paged_attention_mfma.hip", "paged_attention_mfma_stream.hip", "paged_attention_prefill.hip", "paged_attention_prefill32.hip",
            "paged_attention_merge.hip"]
 # packed-fp32 instructions are switched off on purpose for this target
 # The atomic optimizer is switched off: it rewrites an atomic add issued by one lane into a

@@ -94,6 +94,10 @@ hipError_t launch_prefill_mfma(const void *q, const void *k_cache, const void *v
                                const int32_t *block_tables, const int32_t *context_lens,
                                const int32_t *q_start, void *out, const PrefillParams &p,
                                hipStream_t stream);
+hipError_t launch_prefill_mfma32(const void *q, const void *k_cache, const void *v_cache,
+                                 const int32_t *block_tables, const int32_t *context_lens,
+                                 const int32_t *q_start, void *out, const PrefillParams &p,
+                                 hipStream_t stream);
 hipError_t launch_prefill_valu(const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens,
                                const int32_t *q_start, int num_tables, int max_query_len, void *out,

@@ -24,19 +24,19 @@ def make(seed, lens, qlens, hq, hkv, bs=16, dtype=W.BF16, d=128):
     return w, q, q_start
 
 
-def run(w, q, q_start, max_q):
+def run(w, q, q_start, max_q, kernel=0):
     import paper_2503_13773_amd as K
     out = K.paged_attention_prefill(dev_tensor(q, w.dtype), dev_tensor(w.k_cache, w.dtype), dev_tensor(w.v_cache, w.dtype),
                                     torch.from_numpy(w.block_tables).cuda(), torch.from_numpy(w.context_lens).cuda(),
-                                    torch.from_numpy(q_start).cuda(), w.scale, max_q)
+                                    torch.from_numpy(q_start).cuda(), w.scale, max_q, kernel=kernel)
     torch.cuda.synchronize()
     return out
 
 
-def check(oracle_mod, w, q, q_start, label):
-    print(f"[case] prefill {label} lens={w.context_lens.tolist()[:6]} q={np.diff(q_start).tolist()[:6]}", flush=True)
+def check(oracle_mod, w, q, q_start, label, kernel=0):
+    print(f"[case] prefill {label} kernel={kernel} lens={w.context_lens.tolist()[:6]} q={np.diff(q_start).tolist()[:6]}", flush=True)
     max_q = int(np.diff(q_start).max())
-    got = out_to_f64(run(w, q, q_start, max_q))
+    got = out_to_f64(run(w, q, q_start, max_q, kernel))
     ref = oracle_mod.paged_attention_prefill(q, w.k_cache, w.v_cache, w.block_tables, w.context_lens, q_start,
                                              w.scale, dtype=w.dtype, num_threads=8)
     rows = np.concatenate([np.arange(q_start[n], q_start[n + 1]) for n in range(len(w.context_lens))]) \
@@ -52,6 +52,26 @@ def test_full_recompute_matches_oracle(oracle_mod, hq, hkv):
     lens = [1, 5, 16, 17, 63, 64, 65, 130, 300]
     w, q, qs = make(300 + hq, lens, lens, hq, hkv)
     check(oracle_mod, w, q, qs, f"recompute {hq}/{hkv}")
+
+
+@pytest.mark.parametrize("hq,hkv,bs", [(4, 1, 16), (8, 2, 32), (32, 8, 16)])
+def test_small_tile_kernel_on_even_groups(oracle_mod, hq, hkv, bs):
+    """kernel = 2 (KVC_KERNEL_MFMA) asks for the 16x16-tile kernel where the default takes 32x32 tiles:
+    both against the oracle on the same input, and within rounding of each other."""
+    lens = [1, 5, 16, 17, 63, 64, 65, 130, 300, 1000]
+    w, q, qs = make(340 + hq + bs, lens, lens, hq, hkv, bs=bs)
+    check(oracle_mod, w, q, qs, f"16x16 tiles {hq}/{hkv} bs={bs}", kernel=2)
+    check(oracle_mod, w, q, qs, f"32x32 tiles {hq}/{hkv} bs={bs}", kernel=0)
+
+
+def test_negative_scale_takes_the_small_tile_kernel(oracle_mod):
+    """The 32x32-tile kernel takes its max over raw scores and needs a positive scale; any other
+    scale is served by the 16x16-tile kernel."""
+    import dataclasses
+    lens = [40, 130]
+    w, q, qs = make(350, lens, lens, 4, 1)
+    w = dataclasses.replace(w, scale=-w.scale)
+    check(oracle_mod, w, q, qs, "negative scale")
 
 
 def test_chunked_prefill_unaligned_positions(oracle_mod):
