@@ -224,19 +224,20 @@ __device__ inline void turn_barrier() {
 //     chunks  4 ..  7   O block b += V slice 0 . weights 0..7   2 weights each (scores 8 .. 15), rounding, sum
 //                       reads V operand b, slice 1, of step cur
 //     chunks  8 .. 11   S(next) += K operand j . Q, j >= 4
+//                       reads K operand j - 4 of the step after next and V operand j - 4, slice 0, of step next
 //     chunks 12 .. 15   O block b += V slice 1 . weights 8..15  max of S(next)
-//                       reads K operand b of the step after next and V operand b, slice 0, of step next
+//                       requests the K and V rows of the step four ahead (`issue_k`, `issue_v`)
 // so the turn starts with ka_lo = K operands 0 .. 3 of step next and va0 = the slice-0 V
 // operands of step cur in registers and ends with those of the following turn.
 // On return x holds the raw scores of step `next` and the reference point is rebased for it.
 // MASKED: `vlim_cur` = tokens of step cur visible to any column of this wavefront,
 // `limit_next` = tokens of step next visible to this lane's column.
-template <bool MASKED>
+template <bool MASKED, class IssueK, class IssueV>
 __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&ka_lo)[4], uint2 (&va0)[4][2],
                                      const unsigned char *krow1, const unsigned char *krow2,
                                      const unsigned char *sv_cur, const unsigned char *sv_next, const int (&voff)[4],
                                      const bf16x8 (&qb)[8], float scale_log2e, int vlim_cur, int limit_next, int half,
-                                     int c) {
+                                     int c, const IssueK &issue_k, const IssueV &issue_v) {
     const float neg_m = -st.m;
     float pf[16];
     uint32_t w[8];
@@ -255,7 +256,10 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
 #define KVC_QK_LO(J)                                                          \
     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka_lo[J], qb[J], s, 0, 0, 0); \
     ka_hi[J] = read_k_operand<4 + (J)>(krow1, half, c)
-#define KVC_QK_HI(J) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka_hi[J], qb[4 + (J)], s, 0, 0, 0)
+#define KVC_QK_HI(J)                                                                \
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka_hi[J], qb[4 + (J)], s, 0, 0, 0); \
+    ka_lo[J] = read_k_operand<J>(krow2, half, c);                                   \
+    read_v_operand<0>(va0[J], sv_next + voff[J])
 
     KVC_PIN();
     KVC_QK_LO(0); KVC_WEIGHTS(0);
@@ -297,14 +301,14 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
 
 #define KVC_PV1(B)                                                                                        \
     if (MASKED) mask_v_operand<1>(va1[B], vlim_cur, half);                                                \
-    st.acc[B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va1[B]), pb1, st.acc[B], 0, 0, 0);     \
-    ka_lo[B] = read_k_operand<B>(krow2, half, c);                                                         \
-    read_v_operand<0>(va0[B], sv_next + voff[B])
+    st.acc[B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va1[B]), pb1, st.acc[B], 0, 0, 0)
     KVC_PV1(0);
+    issue_k();
     KVC_PIN();
     KVC_PV1(1);
     KVC_PIN();
     KVC_PV1(2);
+    issue_v();
     KVC_PIN();
     KVC_PV1(3);
     rebase(st, take_scores<MASKED>(x, s, limit_next, half), scale_log2e);
@@ -406,25 +410,30 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         }
         return id;
     };
-    // loads the rows of step `src` (the one `id` was looked up for) into the stages of step `step`
-    // loads the rows of step `src` (the one `id` was looked up for) into K stage kst, V stage vst
-    auto issue_loads = [&](int kst, int vst, int src, const Ids &id) __attribute__((always_inline)) {
-        const uint32_t kdst = __builtin_amdgcn_readfirstlane(lds_k0 + kst * kStageBytes);
-        const uint32_t vdst = __builtin_amdgcn_readfirstlane(lds_v0 + vst * kStageBytes);
+    // load the K (V) rows of step `src` (the one `id` was looked up for) into K stage kst (V stage vst)
+    auto issue_rows = [&](const unsigned char *head, uint32_t dst, uint32_t off0, uint32_t off1, int src, const Ids &id)
+                          __attribute__((always_inline)) {
         if (SMALL) {
             const int tok0 = min((2 * src + my_tile) * kTileTokens + lrow, last_pos);
             const int tok1 = min((2 * src + my_tile) * kTileTokens + lrow + 4, last_pos);
             const size_t r0 = size_t(id.a) * block_bytes + size_t(tok0 & (p.block_size - 1)) * 256;
             const size_t r1 = size_t(id.b) * block_bytes + size_t(tok1 & (p.block_size - 1)) * 256;
-            load_lane_to_lds(k_head + r0 + (k_off0 & 255), kdst);
-            load_lane_to_lds(k_head + r1 + (k_off1 & 255), kdst + 1024);
-            load_lane_to_lds(v_head + r0 + (v_off0 & 255), vdst);
-            load_lane_to_lds(v_head + r1 + (v_off0 & 255), vdst + 1024);
+            load_lane_to_lds(head + r0 + (off0 & 255), dst);
+            load_lane_to_lds(head + r1 + (off1 & 255), dst + 1024);
         } else {
             const size_t tile_off = size_t(unsigned(id.a)) * block_bytes + size_t(id.b) * (kTileTokens * 256);
-            load_rows_to_lds(k_head + tile_off, k_off0, k_off1 - 1024, kdst);
-            load_rows_to_lds(v_head + tile_off, v_off0, v_off0, vdst);
+            load_rows_to_lds(head + tile_off, off0, off1 - 1024, dst);
         }
+    };
+    auto issue_k = [&](int kst, int src, const Ids &id) __attribute__((always_inline)) {
+        issue_rows(k_head, __builtin_amdgcn_readfirstlane(lds_k0 + kst * kStageBytes), k_off0, k_off1, src, id);
+    };
+    auto issue_v = [&](int vst, int src, const Ids &id) __attribute__((always_inline)) {
+        issue_rows(v_head, __builtin_amdgcn_readfirstlane(lds_v0 + vst * kStageBytes), v_off0, v_off0 + 1024, src, id);
+    };
+    auto issue_loads = [&](int kst, int vst, int src, const Ids &id) __attribute__((always_inline)) {
+        issue_k(kst, src, id);
+        issue_v(vst, src, id);
     };
 
     // Rows of step j live in K stage j % 4 and V stage j % 5.  Turn s requests step s+4 (over the
@@ -441,6 +450,37 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
     wait_loads_but<4>();  // steps 0 .. 2 have arrived
     __syncthreads();
 
+    int vst = 0;  // V stage of step s
+    int s = 0;
+#define KVC_TURN_BEGIN()                                         \
+    const int vst_next = vst == kVStages - 1 ? 0 : vst + 1;      \
+    const int vst_load = vst == 0 ? kVStages - 1 : vst - 1;      \
+    const int src = min(s + 4, wg_steps - 1);                    \
+    const Ids id = ids;                                          \
+    auto turn_k = [&]() __attribute__((always_inline)) { issue_k(s & 3, src, id); };  \
+    auto turn_v = [&]() __attribute__((always_inline)) {         \
+        issue_v(vst_load, src, id);                              \
+        ids = ids_of(min(s + 5, wg_steps - 1));                  \
+    }
+#define KVC_TURN_END()     \
+    wait_loads_but<4>();   \
+    turn_barrier();        \
+    vst = vst_next
+
+    // Every wavefront of the workgroup passes one more barrier here and wg_steps barriers in its
+    // turns.  A wavefront without query rows only loads and synchronises.
+    if (!active) {
+        __syncthreads();
+        for (; s < wg_steps; ++s) {
+            KVC_TURN_BEGIN();
+            turn_k();
+            turn_v();
+            KVC_TURN_END();
+        }
+        wait_loads_but<0>();
+        return;
+    }
+
     const unsigned char *k_lane = &s_k[0][0] + c * 256;  // this lane's K row inside a stage
     int voff[4];
 #pragma unroll
@@ -448,18 +488,18 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
     float x[16];
     bf16x8 ka_lo[4];
     uint2 va0[4][2];
-    if (active) {  // scores of step 0, then the operands turn 0 starts from
-        floatx16 s;
+    {  // scores of step 0, then the operands turn 0 starts from
+        floatx16 sc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        for (int v = 0; v < 16; ++v) sc[v] = 0.f;
         bf16x8 ka[8];
         ka[0] = read_k_operand<0>(k_lane, half, c); ka[1] = read_k_operand<1>(k_lane, half, c);
         ka[2] = read_k_operand<2>(k_lane, half, c); ka[3] = read_k_operand<3>(k_lane, half, c);
         ka[4] = read_k_operand<4>(k_lane, half, c); ka[5] = read_k_operand<5>(k_lane, half, c);
         ka[6] = read_k_operand<6>(k_lane, half, c); ka[7] = read_k_operand<7>(k_lane, half, c);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], s, 0, 0, 0);
-        rebase(st, take_scores<true>(x, s, my_pos + 1, half), p.scale_log2e);
+        for (int j = 0; j < 8; ++j) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], sc, 0, 0, 0);
+        rebase(st, take_scores<true>(x, sc, my_pos + 1, half), p.scale_log2e);
         const unsigned char *krow = k_lane + kStageBytes;
         ka_lo[0] = read_k_operand<0>(krow, half, c); ka_lo[1] = read_k_operand<1>(krow, half, c);
         ka_lo[2] = read_k_operand<2>(krow, half, c); ka_lo[3] = read_k_operand<3>(krow, half, c);
@@ -469,42 +509,26 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
     __syncthreads();  // K stage 0 has been read: turn 0 may load step 4 over it
 
     // The turns below the diagonal first (no mask), then the one to three turns that the causal
-    // mask touches; a wavefront without query rows only loads and synchronises.  Every wavefront
-    // of the workgroup passes wg_steps barriers.
-    int vst = 0;  // V stage of step s
-    const int plain_turns = active ? min(max(free_steps - 1, 0), wg_steps) : 0;
-    const int masked_end = active ? wg_steps : 0;
-    int s = 0;
-#define KVC_TURN_LOADS()                                                                           \
-    const int vst_next = vst == kVStages - 1 ? 0 : vst + 1;                                        \
-    issue_loads(s & 3, vst == 0 ? kVStages - 1 : vst - 1, min(s + 4, wg_steps - 1), ids);          \
-    ids = ids_of(min(s + 5, wg_steps - 1))
-#define KVC_TURN_END()     \
-    wait_loads_but<4>();   \
-    turn_barrier();        \
-    vst = vst_next
+    // mask touches.
+    const int plain_turns = min(max(free_steps - 1, 0), wg_steps);
     for (; s < plain_turns; ++s) {
-        KVC_TURN_LOADS();
+        KVC_TURN_BEGIN();
         pipeline_turn<false>(st, x, ka_lo, va0, k_lane + ((s + 1) & 3) * kStageBytes, k_lane + ((s + 2) & 3) * kStageBytes,
-                             &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, kStepTokens, kStepTokens, half, c);
-        KVC_TURN_END();
-    }
-    for (; s < masked_end; ++s) {
-        KVC_TURN_LOADS();
-        pipeline_turn<true>(st, x, ka_lo, va0, k_lane + ((s + 1) & 3) * kStageBytes, k_lane + ((s + 2) & 3) * kStageBytes,
-                            &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, wave_vis - s * kStepTokens,
-                            my_pos + 1 - (s + 1) * kStepTokens, half, c);
+                             &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, kStepTokens, kStepTokens, half, c,
+                             turn_k, turn_v);
         KVC_TURN_END();
     }
     for (; s < wg_steps; ++s) {
-        KVC_TURN_LOADS();
+        KVC_TURN_BEGIN();
+        pipeline_turn<true>(st, x, ka_lo, va0, k_lane + ((s + 1) & 3) * kStageBytes, k_lane + ((s + 2) & 3) * kStageBytes,
+                            &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, wave_vis - s * kStepTokens,
+                            my_pos + 1 - (s + 1) * kStepTokens, half, c, turn_k, turn_v);
         KVC_TURN_END();
     }
-#undef KVC_TURN_LOADS
+#undef KVC_TURN_BEGIN
 #undef KVC_TURN_END
     wait_loads_but<0>();  // nothing may still be landing in LDS when the workgroup's LDS is handed on
 
-    if (!active) return;
     // lane (half, c) holds O[query row i0 + r][head0 + (c >> 4)][32*b + 8*a + 4*half .. +3] in acc[b][4a .. 4a+3]
     const float inv = 1.0f / sum_over_halves(st.lsum);
     if (r < nrows) {
