@@ -17,14 +17,14 @@
 // a score tile), one barrier per step.
 //
 // K and V rows travel from the cache straight into LDS (global_load_lds_dwordx4: lane l of a
-// wavefront writes its 16 bytes at M0 + 16 * l, no register staging), requested four steps
-// before the step's P.V product, so a request has two whole turns to arrive; which bytes a
+// wavefront writes its 16 bytes at M0 + 16 * l, no register staging), requested two turns
+// before their first use (K rows four steps ahead, V rows three); which bytes a
 // lane fetches is chosen so that the LDS image is
 //   K rows: 16-byte chunks XOR-permuted by the row number (A-operand reads of 16 rows x the
 //           same dims then touch every bank once);
 //   V rows: 64-byte granules rotated by the row number (the 4 rows x 64 bytes that a
 //           half-wavefront reads in one transposing access then fall into disjoint banks).
-// Four steps of K and five of V are in LDS (72 KiB).
+// Four steps of K and four of V are in LDS (64 KiB).
 //
 // Per step, with lane = 32 * half + c:
 //   S^T = K . Q^T      8 x v_mfma_f32_32x32x16_bf16 (depth = the 128 dims).  A: K row c of the
@@ -66,7 +66,7 @@ constexpr int kStepTokens = 32;
 constexpr int kStageBytes = kStepTokens * D * 2;  // K (or V) rows of a step: 32 rows x 256 bytes
 constexpr float kLazyLog2 = 8.0f;
 constexpr int kKStages = 4;   // K rows of steps s+1 .. s+4 during turn s
-constexpr int kVStages = 5;   // V rows of steps s .. s+4
+constexpr int kVStages = 4;   // V rows of steps s .. s+3
 
 // Online-softmax state of one column (query row x head); lane (half, c) holds
 // O[column c][32*b + 8*(v/4) + 4*half + v%4] in acc[b][v].
@@ -436,43 +436,48 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         issue_v(vst, src, id);
     };
 
-    // Rows of step j live in K stage j % 4 and V stage j % 5.  Turn s requests step s+4 (over the
-    // K rows of step s, last read during turn s-1, and the V rows of step s-1, last read during
-    // turn s-1), multiplies with operands of steps s+1 (K) and s (V) and reads operands of steps
-    // s+1, s+2 (K) and s, s+1 (V).  Before the barrier that ends it, it waits for its own loads of
-    // turn s-1 (step s+3): the barrier publishes them for turn s+1.  Past the last step the last
-    // one is loaded again (unused): the loop stays branch free.
-    issue_loads(0, 0, 0, ids_of(0));
-    issue_loads(1, 1, min(1, wg_steps - 1), ids_of(min(1, wg_steps - 1)));
-    issue_loads(2, 2, min(2, wg_steps - 1), ids_of(min(2, wg_steps - 1)));
-    issue_loads(3, 3, min(3, wg_steps - 1), ids_of(min(3, wg_steps - 1)));
-    Ids ids = ids_of(min(4, wg_steps - 1));
-    wait_loads_but<4>();  // steps 0 .. 2 have arrived
+    // Rows of step j live in K stage j % 4 and V stage j % 4.  Turn s requests the K rows of step
+    // s+4 (over those of step s, last read during turn s-1) and the V rows of step s+3 (over those
+    // of step s-1, last read during turn s-1), multiplies with operands of steps s+1 (K) and s (V)
+    // and reads operands of steps s+1, s+2 (K) and s, s+1 (V).  Before the barrier that ends it, it
+    // waits for its own loads of turn s-1: the barrier publishes them for turn s+1.  Past the last
+    // step the last one is loaded again (unused): the loop stays branch free.
+    Ids ids_v;
+    {
+        const Ids i0s = ids_of(0), i1s = ids_of(min(1, wg_steps - 1)), i2s = ids_of(min(2, wg_steps - 1));
+        ids_v = ids_of(min(3, wg_steps - 1));
+        issue_loads(0, 0, 0, i0s);
+        issue_loads(1, 1, min(1, wg_steps - 1), i1s);
+        issue_loads(2, 2, min(2, wg_steps - 1), i2s);
+        issue_k(3, min(3, wg_steps - 1), ids_v);
+    }
+    Ids ids_k = ids_of(min(4, wg_steps - 1));
+    wait_loads_but<2>();  // steps 0 .. 2 have arrived
     __syncthreads();
 
-    int vst = 0;  // V stage of step s
     int s = 0;
-#define KVC_TURN_BEGIN()                                         \
-    const int vst_next = vst == kVStages - 1 ? 0 : vst + 1;      \
-    const int vst_load = vst == 0 ? kVStages - 1 : vst - 1;      \
-    const int src = min(s + 4, wg_steps - 1);                    \
-    const Ids id = ids;                                          \
-    auto turn_k = [&]() __attribute__((always_inline)) { issue_k(s & 3, src, id); };  \
-    auto turn_v = [&]() __attribute__((always_inline)) {         \
-        issue_v(vst_load, src, id);                              \
-        ids = ids_of(min(s + 5, wg_steps - 1));                  \
+    // PH = s % 4 (a literal in the unrolled loop: every LDS address of the turn is then a per-lane
+    // register plus an immediate)
+#define KVC_TURN_BEGIN(PH)                                                                        \
+    const int ph = (PH);                                                                          \
+    const int src_k = min(s + 4, wg_steps - 1), src_v = min(s + 3, wg_steps - 1);                 \
+    const Ids idk = ids_k, idv = ids_v;                                                           \
+    auto turn_k = [&]() __attribute__((always_inline)) { issue_k(ph, src_k, idk); };              \
+    auto turn_v = [&]() __attribute__((always_inline)) {                                          \
+        issue_v((ph + 3) & 3, src_v, idv);                                                        \
+        ids_v = idk;                                                                              \
+        ids_k = ids_of(min(s + 5, wg_steps - 1));                                                 \
     }
 #define KVC_TURN_END()     \
     wait_loads_but<4>();   \
-    turn_barrier();        \
-    vst = vst_next
+    turn_barrier()
 
     // Every wavefront of the workgroup passes one more barrier here and wg_steps barriers in its
     // turns.  A wavefront without query rows only loads and synchronises.
     if (!active) {
         __syncthreads();
         for (; s < wg_steps; ++s) {
-            KVC_TURN_BEGIN();
+            KVC_TURN_BEGIN(s & 3);
             turn_k();
             turn_v();
             KVC_TURN_END();
@@ -508,23 +513,29 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
     }
     __syncthreads();  // K stage 0 has been read: turn 0 may load step 4 over it
 
-    // The turns below the diagonal first (no mask), then the one to three turns that the causal
-    // mask touches.
+    // The turns below the diagonal first (no mask), unrolled by the four phases of the stage
+    // rings, then the one to three turns that the causal mask touches.
+    const unsigned char *v_base = &s_v[0][0];
+#define KVC_TURN(MASKED, PH, VLIM, LIMIT)                                                                      \
+    {                                                                                                          \
+        KVC_TURN_BEGIN(PH);                                                                                    \
+        pipeline_turn<MASKED>(st, x, ka_lo, va0, k_lane + ((ph + 1) & 3) * kStageBytes,                        \
+                              k_lane + ((ph + 2) & 3) * kStageBytes, v_base + ph * kStageBytes,                \
+                              v_base + ((ph + 1) & 3) * kStageBytes, voff, qb, p.scale_log2e, VLIM, LIMIT,     \
+                              half, c, turn_k, turn_v);                                                        \
+        KVC_TURN_END();                                                                                        \
+        ++s;                                                                                                   \
+    }
     const int plain_turns = min(max(free_steps - 1, 0), wg_steps);
-    for (; s < plain_turns; ++s) {
-        KVC_TURN_BEGIN();
-        pipeline_turn<false>(st, x, ka_lo, va0, k_lane + ((s + 1) & 3) * kStageBytes, k_lane + ((s + 2) & 3) * kStageBytes,
-                             &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, kStepTokens, kStepTokens, half, c,
-                             turn_k, turn_v);
-        KVC_TURN_END();
+    while (s + 4 <= plain_turns) {
+        KVC_TURN(false, 0, kStepTokens, kStepTokens)
+        KVC_TURN(false, 1, kStepTokens, kStepTokens)
+        KVC_TURN(false, 2, kStepTokens, kStepTokens)
+        KVC_TURN(false, 3, kStepTokens, kStepTokens)
     }
-    for (; s < wg_steps; ++s) {
-        KVC_TURN_BEGIN();
-        pipeline_turn<true>(st, x, ka_lo, va0, k_lane + ((s + 1) & 3) * kStageBytes, k_lane + ((s + 2) & 3) * kStageBytes,
-                            &s_v[vst][0], &s_v[vst_next][0], voff, qb, p.scale_log2e, wave_vis - s * kStepTokens,
-                            my_pos + 1 - (s + 1) * kStepTokens, half, c, turn_k, turn_v);
-        KVC_TURN_END();
-    }
+    while (s < plain_turns) KVC_TURN(false, s & 3, kStepTokens, kStepTokens)
+    while (s < wg_steps) KVC_TURN(true, s & 3, wave_vis - s * kStepTokens, my_pos + 1 - (s + 1) * kStepTokens)
+#undef KVC_TURN
 #undef KVC_TURN_BEGIN
 #undef KVC_TURN_END
     wait_loads_but<0>();  // nothing may still be landing in LDS when the workgroup's LDS is handed on
