@@ -195,6 +195,9 @@ __device__ inline void load_rows_to_lds(const void *base, uint32_t off0, uint32_
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\tglobal_load_lds_dwordx4 %2, %3 offset:1024"
                  :: "s"(lds_addr), "v"(off0), "v"(off1_minus_1k), "s"(base) : "memory");
 }
+__device__ inline void load_row_group_to_lds(const void *base, uint32_t off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds_addr), "v"(off), "s"(base) : "memory");
+}
 __device__ inline void load_lane_to_lds(const void *addr, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds_addr), "v"(addr) : "memory");
 }
@@ -207,6 +210,14 @@ __device__ inline void wait_loads_but() {
 // requested for the next turn): the loads of the next turn overwrite the stages they come from.
 __device__ inline void turn_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// The barrier in the middle of a turn orders no data (see the kernel): it only keeps the two
+// groups of wavefronts half a turn apart.
+__device__ inline void phase_barrier() {
+    asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
@@ -232,14 +243,14 @@ __device__ inline void turn_barrier() {
 // On return x holds the raw scores of step `next` and the reference point is rebased for it.
 // MASKED: `vlim_cur` = tokens of step cur visible to any column of this wavefront,
 // `limit_next` = tokens of step next visible to this lane's column.
-template <bool MASKED, class IssueK, class IssueV>
+template <bool MASKED, class IssueK, class IssueV, class Mid>
 __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&ka_lo)[4], uint2 (&va0)[4][2],
                                      const unsigned char *krow1, const unsigned char *krow2,
                                      const unsigned char *sv_cur, const unsigned char *sv_next, const int (&voff)[4],
                                      const bf16x8 (&qb)[8], float scale_log2e, int vlim_cur, int limit_next, int half,
-                                     int c, const IssueK &issue_k, const IssueV &issue_v) {
+                                     int c, const IssueK &issue_k, const IssueV &issue_v, const Mid &mid) {
     const float neg_m = -st.m;
-    float pf[16];
+    float arg[16], pf[16], pair[8];
     uint32_t w[8];
     bf16x8 ka_hi[4];
     uint2 va1[4][2];
@@ -247,12 +258,19 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
 #pragma unroll
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
 
-#define KVC_WEIGHTS(V)                                                                   \
-    pf[V] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[V], scale_log2e, neg_m));            \
-    pf[(V) + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[(V) + 1], scale_log2e, neg_m))
-#define KVC_ROUND(I)                                \
-    w[I] = pack_bf16(pf[2 * (I)], pf[2 * (I) + 1]); \
-    st.lsum += pf[2 * (I)] + pf[2 * (I) + 1]
+    // The softmax arithmetic of score pair P goes through four stages placed in different chunks,
+    // so that no instruction waits for the result of the one in front of it: exponent arguments,
+    // exponentials, rounding to bf16 plus the pair's sum, and the addition to the normaliser.
+#define KVC_ARG(P)                                                           \
+    arg[2 * (P)] = __builtin_fmaf(x[2 * (P)], scale_log2e, neg_m);           \
+    arg[2 * (P) + 1] = __builtin_fmaf(x[2 * (P) + 1], scale_log2e, neg_m)
+#define KVC_EXP(P)                                        \
+    pf[2 * (P)] = __builtin_amdgcn_exp2f(arg[2 * (P)]);   \
+    pf[2 * (P) + 1] = __builtin_amdgcn_exp2f(arg[2 * (P) + 1])
+#define KVC_ROUND(P)                                \
+    w[P] = pack_bf16(pf[2 * (P)], pf[2 * (P) + 1]); \
+    pair[P] = pf[2 * (P)] + pf[2 * (P) + 1]
+#define KVC_SUM(P) st.lsum += pair[P]
 #define KVC_QK_LO(J)                                                          \
     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka_lo[J], qb[J], s, 0, 0, 0); \
     ka_hi[J] = read_k_operand<4 + (J)>(krow1, half, c)
@@ -262,13 +280,13 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
     read_v_operand<0>(va0[J], sv_next + voff[J])
 
     KVC_PIN();
-    KVC_QK_LO(0); KVC_WEIGHTS(0);
+    KVC_QK_LO(0); KVC_ARG(0); KVC_ARG(1); KVC_EXP(0);
     KVC_PIN();
-    KVC_QK_LO(1); KVC_WEIGHTS(2); KVC_ROUND(0);
+    KVC_QK_LO(1); KVC_ARG(2); KVC_EXP(1); KVC_ROUND(0);
     KVC_PIN();
-    KVC_QK_LO(2); KVC_WEIGHTS(4); KVC_ROUND(1);
+    KVC_QK_LO(2); KVC_ARG(3); KVC_EXP(2); KVC_ROUND(1); KVC_SUM(0);
     KVC_PIN();
-    KVC_QK_LO(3); KVC_WEIGHTS(6); KVC_ROUND(2);
+    KVC_QK_LO(3); KVC_EXP(3); KVC_ROUND(2); KVC_SUM(1); KVC_ARG(4);
     KVC_PIN();
     KVC_ROUND(3);
     const uint4 pw0 = {w[0], w[1], w[2], w[3]};
@@ -278,27 +296,29 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
     if (MASKED) mask_v_operand<0>(va0[B], vlim_cur, half);                                                \
     st.acc[B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va0[B]), pb0, st.acc[B], 0, 0, 0);     \
     read_v_operand<1>(va1[B], sv_cur + voff[B])
-    KVC_PV0(0); KVC_WEIGHTS(8);
+    KVC_PV0(0); KVC_SUM(2); KVC_ARG(5); KVC_EXP(4); KVC_SUM(3);
     KVC_PIN();
-    KVC_PV0(1); KVC_WEIGHTS(10); KVC_ROUND(4);
+    KVC_PV0(1); KVC_ARG(6); KVC_EXP(5); KVC_ROUND(4);
     KVC_PIN();
-    KVC_PV0(2); KVC_WEIGHTS(12); KVC_ROUND(5);
+    KVC_PV0(2); KVC_ARG(7); KVC_EXP(6); KVC_ROUND(5); KVC_SUM(4);
     KVC_PIN();
-    KVC_PV0(3); KVC_WEIGHTS(14); KVC_ROUND(6);
+    KVC_PV0(3); KVC_EXP(7); KVC_ROUND(6); KVC_SUM(5);
     KVC_PIN();
-    KVC_ROUND(7);
+    mid();  // the workgroup's half-turn barrier: the other group of wavefronts changes phase here too
+    KVC_PIN();
+
+    KVC_QK_HI(0); KVC_ROUND(7); KVC_SUM(6);
+    KVC_PIN();
     const uint4 pw1 = {w[4], w[5], w[6], w[7]};
     const bf16x8 pb1 = __builtin_bit_cast(bf16x8, pw1);
-
-    KVC_QK_HI(0);
-    KVC_PIN();
-    KVC_QK_HI(1);
+    KVC_QK_HI(1); KVC_SUM(7);
     KVC_PIN();
     KVC_QK_HI(2);
     KVC_PIN();
     KVC_QK_HI(3);
     KVC_PIN();
 
+    // chunks 12 .. 15 also take the raw scores of step next (masked if need be) and their max
 #define KVC_PV1(B)                                                                                        \
     if (MASKED) mask_v_operand<1>(va1[B], vlim_cur, half);                                                \
     st.acc[B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va1[B]), pb1, st.acc[B], 0, 0, 0)
@@ -306,13 +326,25 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
     issue_k();
     KVC_PIN();
     KVC_PV1(1);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        x[v] = s[v];
+        if (MASKED && 8 * (v >> 2) + 4 * half + (v & 3) >= limit_next) x[v] = -INFINITY;
+    }
+    const float m0 = max3(x[0], x[1], x[2]), m1 = max3(x[3], x[4], x[5]), m2 = max3(x[6], x[7], x[8]);
     KVC_PIN();
     KVC_PV1(2);
     issue_v();
+    const float m3 = max3(x[9], x[10], x[11]), m4 = max3(x[12], x[13], x[14]);
     KVC_PIN();
     KVC_PV1(3);
-    rebase(st, take_scores<MASKED>(x, s, limit_next, half), scale_log2e);
-#undef KVC_WEIGHTS
+    const float m5 = max3(m0, m1, m2), m6 = max3(m3, m4, x[15]);
+    float lane_max;
+    asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(m5), "v"(m6));
+    rebase(st, lane_max, scale_log2e);
+#undef KVC_ARG
+#undef KVC_EXP
+#undef KVC_SUM
 #undef KVC_ROUND
 #undef KVC_QK_LO
 #undef KVC_QK_HI
@@ -320,42 +352,49 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
 #undef KVC_PV1
 }
 
-template <bool SMALL>
-__global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
+// GROUPS = 1: workgroups of four wavefronts (64 query rows), two per compute unit.  GROUPS = 2:
+// workgroups of two groups of four wavefronts (128 query rows), one per compute unit; the groups
+// run half a turn apart (see below).  Either way a SIMD holds two wavefronts.
+template <bool SMALL, int GROUPS>
+__global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
     const int32_t *__restrict__ context_lens, const int32_t *__restrict__ q_start,
-    uint16_t *__restrict__ out, PrefillParams p) {
+    uint16_t *__restrict__ out, PrefillParams p, int query_tiles) {
     __shared__ __attribute__((aligned(1024))) unsigned char s_k[kKStages][kStageBytes];
     __shared__ __attribute__((aligned(1024))) unsigned char s_v[kVStages][kStageBytes];
+    constexpr int kTileRows = 64 * GROUPS;          // query rows of a workgroup: 16 per wavefront
+    constexpr int kLoads = 2 / GROUPS;              // 1 KiB loads of K (and of V) per wavefront and step
+    constexpr int kWavesPerTile = 2 * GROUPS;       // wavefronts that share a 16-row tile of a step
 
     // blockIdx.x = head pair + pairs * (seq + num_seqs * reversed query tile)
     const int chunks = p.num_q_heads / 2;
     const int item = blockIdx.x;
     const int chunk = item % chunks;
     const int n = (item / chunks) % p.num_seqs;
-    const int qtile = p.max_query_tiles - 1 - item / (chunks * p.num_seqs);
+    const int qtile = query_tiles - 1 - item / (chunks * p.num_seqs);
     const int head0 = chunk * 2;
     const int kvh = head0 / p.group;
 
     const int S = context_lens[n];
     const int qs = q_start[n];
     const int Qn = q_start[n + 1] - qs;
-    if (qtile * 64 >= Qn || Qn > S) return;  // uniform over the workgroup
+    if (qtile * kTileRows >= Qn || Qn > S) return;  // uniform over the workgroup
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int group = wave >> 2;  // GROUPS = 2: wavefronts w and w + 4 share a SIMD; group 1 runs half a turn behind group 0
     const int half = lane >> 5, c = lane & 31;
     const int r = c & 15;  // query row of the column inside the wavefront's 16; c >> 4 = its head
 
     // tiles and steps this workgroup walks (up to the position of its last query row)
-    const int last_pos = S - Qn + min(Qn, qtile * 64 + 64) - 1;
+    const int last_pos = S - Qn + min(Qn, qtile * kTileRows + kTileRows) - 1;
     const int wg_tiles = (last_pos >> 4) + 1;
     const int wg_steps = (wg_tiles + 1) / 2;
     const int32_t *table = block_tables + size_t(n) * p.max_blocks_per_seq;
 
-    // wavefronts past the last query row still fetch and synchronise, they just never compute
-    const int i0 = qtile * 64 + 16 * wave;  // first query row of this wavefront
+    // wavefronts past the last query row still load and synchronise, they just never compute
+    const int i0 = qtile * kTileRows + 16 * wave;  // first query row of this wavefront
     const bool active = i0 < Qn;
     const int nrows = active ? min(16, Qn - i0) : 1;
     const int row = min(r, nrows - 1);      // lanes past the last query row shadow it
@@ -374,35 +413,34 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
     ColumnState st;
     st.reset();
 
-    // ---- this wavefront's share of a step's rows: rows 8 * wave .. + 7 of the 32 (they lie in
-    // one 16-token tile, number wave / 2 of the step), as two loads of 4 rows for K and two for
-    // V.  Lane l writes LDS chunk l % 16 of row 8 * wave + 4 * i + l / 16 (load i); the chunk
-    // it fetches for that place follows from the stage layouts.
+    // ---- this wavefront's share of a step's rows: 4 * kLoads consecutive rows of the 32 (inside
+    // one 16-row tile of the step), kLoads loads of 4 rows for K and as many for V.  Lane l of
+    // load i writes LDS chunk l % 16 of the share's row 4 * i + l / 16; the chunk it fetches for
+    // that place follows from the stage layouts.
     const size_t head_bytes = size_t(p.block_size) * D * 2;
     const size_t block_bytes = head_bytes * p.num_kv_heads;
     const unsigned char *k_head = reinterpret_cast<const unsigned char *>(k_cache) + size_t(kvh) * head_bytes;
     const unsigned char *v_head = reinterpret_cast<const unsigned char *>(v_cache) + size_t(kvh) * head_bytes;
     const int sub_mask = (1 << p.tiles_per_block_log2) - 1;
-    const int my_tile = wave >> 1;               // tile of the step this wavefront loads from
-    const int lrow = 8 * (wave & 1) + (lane >> 4);  // row inside the tile of load 0 (load 1: + 4)
+    const int my_tile = wave / kWavesPerTile;       // tile of the step this wavefront loads from
+    const int lrow = 4 * kLoads * (wave % kWavesPerTile) + (lane >> 4);  // row inside the tile of load 0 (load 1: + 4)
     const int lchunk = lane & 15;
-    const uint32_t k_off0 = lrow * 256 + ((lchunk ^ lrow) << 4);
+    const uint32_t k_off = lrow * 256 + ((lchunk ^ lrow) << 4);
     const uint32_t k_off1 = (lrow + 4) * 256 + ((lchunk ^ (lrow + 4)) << 4);
-    const uint32_t v_off0 = lrow * 256 + ((4 * (((lchunk >> 2) - lrow) & 3) + (lchunk & 3)) << 4);  // load 1: + 1024
-    const uint32_t lds_k0 = uint32_t(reinterpret_cast<uintptr_t>(&s_k[0][0])) + 2048 * wave;
-    const uint32_t lds_v0 = uint32_t(reinterpret_cast<uintptr_t>(&s_v[0][0])) + 2048 * wave;
+    const uint32_t v_off = lrow * 256 + ((4 * (((lchunk >> 2) - lrow) & 3) + (lchunk & 3)) << 4);  // load 1: + 1024
+    const uint32_t lds_k0 = uint32_t(reinterpret_cast<uintptr_t>(&s_k[0][0])) + 1024 * kLoads * wave;
+    const uint32_t lds_v0 = uint32_t(reinterpret_cast<uintptr_t>(&s_v[0][0])) + 1024 * kLoads * wave;
 
     // Large blocks: the block id of the wavefront's tile is uniform, it comes through the scalar
     // cache one turn before the loads that use it.  Tiles past the last one repeat it (never
-    // used unmasked).  Small blocks: a / b are the blocks of this lane's row in the two loads.
+    // used unmasked).  Small blocks: a / b are the blocks of this lane's row in loads 0 / 1.
     struct Ids { int a, b; };
     auto ids_of = [&](int step) __attribute__((always_inline)) -> Ids {
         Ids id;
         if (SMALL) {
-            const int tok0 = min((2 * step + my_tile) * kTileTokens + lrow, last_pos);
-            const int tok1 = min((2 * step + my_tile) * kTileTokens + lrow + 4, last_pos);
-            id.a = table[tok0 >> p.block_size_log2];
-            id.b = table[tok1 >> p.block_size_log2];
+            const int tok = min((2 * step + my_tile) * kTileTokens + lrow, last_pos);
+            id.a = table[tok >> p.block_size_log2];
+            id.b = kLoads == 2 ? table[min(tok + 4, last_pos) >> p.block_size_log2] : 0;
         } else {
             const int t = min(2 * step + my_tile, wg_tiles - 1);
             id.a = __builtin_amdgcn_readfirstlane(table[t >> p.tiles_per_block_log2]);
@@ -410,49 +448,55 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         }
         return id;
     };
-    // load the K (V) rows of step `src` (the one `id` was looked up for) into K stage kst (V stage vst)
-    auto issue_rows = [&](const unsigned char *head, uint32_t dst, uint32_t off0, uint32_t off1, int src, const Ids &id)
+    // load this wavefront's K (V) rows of step `src` (the one `id` was looked up for) into a stage
+    auto issue_rows = [&](const unsigned char *head, uint32_t dst, uint32_t off, uint32_t off1, int src, const Ids &id)
                           __attribute__((always_inline)) {
         if (SMALL) {
-            const int tok0 = min((2 * src + my_tile) * kTileTokens + lrow, last_pos);
-            const int tok1 = min((2 * src + my_tile) * kTileTokens + lrow + 4, last_pos);
-            const size_t r0 = size_t(id.a) * block_bytes + size_t(tok0 & (p.block_size - 1)) * 256;
-            const size_t r1 = size_t(id.b) * block_bytes + size_t(tok1 & (p.block_size - 1)) * 256;
-            load_lane_to_lds(head + r0 + (off0 & 255), dst);
-            load_lane_to_lds(head + r1 + (off1 & 255), dst + 1024);
+            const int tok = min((2 * src + my_tile) * kTileTokens + lrow, last_pos);
+            load_lane_to_lds(head + size_t(id.a) * block_bytes + size_t(tok & (p.block_size - 1)) * 256 + (off & 255), dst);
+            if (kLoads == 2) {
+                const int tok1 = min(tok + 4, last_pos);
+                load_lane_to_lds(head + size_t(id.b) * block_bytes + size_t(tok1 & (p.block_size - 1)) * 256 + (off1 & 255),
+                                 dst + 1024);
+            }
         } else {
-            const size_t tile_off = size_t(unsigned(id.a)) * block_bytes + size_t(id.b) * (kTileTokens * 256);
-            load_rows_to_lds(head + tile_off, off0, off1 - 1024, dst);
+            const unsigned char *tile = head + size_t(unsigned(id.a)) * block_bytes + size_t(id.b) * (kTileTokens * 256);
+            if (kLoads == 2) load_rows_to_lds(tile, off, off1 - 1024, dst);
+            else load_row_group_to_lds(tile, off, dst);
         }
     };
     auto issue_k = [&](int kst, int src, const Ids &id) __attribute__((always_inline)) {
-        issue_rows(k_head, __builtin_amdgcn_readfirstlane(lds_k0 + kst * kStageBytes), k_off0, k_off1, src, id);
+        issue_rows(k_head, __builtin_amdgcn_readfirstlane(lds_k0 + kst * kStageBytes), k_off, k_off1, src, id);
     };
     auto issue_v = [&](int vst, int src, const Ids &id) __attribute__((always_inline)) {
-        issue_rows(v_head, __builtin_amdgcn_readfirstlane(lds_v0 + vst * kStageBytes), v_off0, v_off0 + 1024, src, id);
-    };
-    auto issue_loads = [&](int kst, int vst, int src, const Ids &id) __attribute__((always_inline)) {
-        issue_k(kst, src, id);
-        issue_v(vst, src, id);
+        issue_rows(v_head, __builtin_amdgcn_readfirstlane(lds_v0 + vst * kStageBytes), v_off, v_off + 1024, src, id);
     };
 
     // Rows of step j live in K stage j % 4 and V stage j % 4.  Turn s requests the K rows of step
-    // s+4 (over those of step s, last read during turn s-1) and the V rows of step s+3 (over those
-    // of step s-1, last read during turn s-1), multiplies with operands of steps s+1 (K) and s (V)
-    // and reads operands of steps s+1, s+2 (K) and s, s+1 (V).  Before the barrier that ends it, it
-    // waits for its own loads of turn s-1: the barrier publishes them for turn s+1.  Past the last
-    // step the last one is loaded again (unused): the loop stays branch free.
+    // s+4 (over those of step s) and the V rows of step s+3 (over those of step s-1), multiplies
+    // with operands of steps s+1 (K) and s (V) and reads operands of steps s+1, s+2 (K) and s, s+1
+    // (V).  Before the barrier that ends it, a wavefront waits for its own loads of turn s-1 and
+    // for its LDS reads.  The workgroup meets at a barrier twice per turn, and group 1 of its
+    // wavefronts runs half a turn behind group 0: while one wavefront of a SIMD is in the first,
+    // vector-heavy half of a turn the other is in the second, matrix-heavy half.  A stage is
+    // overwritten, at the earliest, two barriers after the last wavefront has waited for its
+    // reads of it, and read, at the earliest, after the barrier that follows the wait of the last
+    // wavefront for its loads into it.  Past the last step the last one is loaded again (unused):
+    // the loops stay branch free.
     Ids ids_v;
     {
         const Ids i0s = ids_of(0), i1s = ids_of(min(1, wg_steps - 1)), i2s = ids_of(min(2, wg_steps - 1));
         ids_v = ids_of(min(3, wg_steps - 1));
-        issue_loads(0, 0, 0, i0s);
-        issue_loads(1, 1, min(1, wg_steps - 1), i1s);
-        issue_loads(2, 2, min(2, wg_steps - 1), i2s);
+        issue_k(0, 0, i0s);
+        issue_v(0, 0, i0s);
+        issue_k(1, min(1, wg_steps - 1), i1s);
+        issue_v(1, min(1, wg_steps - 1), i1s);
+        issue_k(2, min(2, wg_steps - 1), i2s);
+        issue_v(2, min(2, wg_steps - 1), i2s);
         issue_k(3, min(3, wg_steps - 1), ids_v);
     }
     Ids ids_k = ids_of(min(4, wg_steps - 1));
-    wait_loads_but<2>();  // steps 0 .. 2 have arrived
+    wait_loads_but<kLoads>();  // steps 0 .. 2 have arrived
     __syncthreads();
 
     int s = 0;
@@ -469,19 +513,23 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         ids_k = ids_of(min(s + 5, wg_steps - 1));                                                 \
     }
 #define KVC_TURN_END()     \
-    wait_loads_but<4>();   \
+    wait_loads_but<2 * kLoads>();   \
     turn_barrier()
 
-    // Every wavefront of the workgroup passes one more barrier here and wg_steps barriers in its
-    // turns.  A wavefront without query rows only loads and synchronises.
+    // Every wavefront of the workgroup passes one more barrier here, two per turn, and one to
+    // set group 1 back by half a turn (group 0 passes its counterpart after its last turn).  A
+    // wavefront without query rows only loads and synchronises.
     if (!active) {
         __syncthreads();
+        if (GROUPS == 2 && group == 1) phase_barrier();
         for (; s < wg_steps; ++s) {
             KVC_TURN_BEGIN(s & 3);
+            if (GROUPS == 2) phase_barrier();
             turn_k();
             turn_v();
             KVC_TURN_END();
         }
+        if (GROUPS == 2 && group == 0) phase_barrier();
         wait_loads_but<0>();
         return;
     }
@@ -512,17 +560,21 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         for (int b = 0; b < 4; ++b) read_v_operand<0>(va0[b], &s_v[0][0] + voff[b]);
     }
     __syncthreads();  // K stage 0 has been read: turn 0 may load step 4 over it
+    if (GROUPS == 2 && group == 1) phase_barrier();
 
     // The turns below the diagonal first (no mask), unrolled by the four phases of the stage
     // rings, then the one to three turns that the causal mask touches.
     const unsigned char *v_base = &s_v[0][0];
+    auto mid = []() __attribute__((always_inline)) {
+        if (GROUPS == 2) phase_barrier();
+    };
 #define KVC_TURN(MASKED, PH, VLIM, LIMIT)                                                                      \
     {                                                                                                          \
         KVC_TURN_BEGIN(PH);                                                                                    \
         pipeline_turn<MASKED>(st, x, ka_lo, va0, k_lane + ((ph + 1) & 3) * kStageBytes,                        \
                               k_lane + ((ph + 2) & 3) * kStageBytes, v_base + ph * kStageBytes,                \
                               v_base + ((ph + 1) & 3) * kStageBytes, voff, qb, p.scale_log2e, VLIM, LIMIT,     \
-                              half, c, turn_k, turn_v);                                                        \
+                              half, c, turn_k, turn_v, mid);                                                   \
         KVC_TURN_END();                                                                                        \
         ++s;                                                                                                   \
     }
@@ -534,10 +586,21 @@ __global__ __launch_bounds__(kThreads, 2) void pa_prefill_mfma32_kernel(
         KVC_TURN(false, 3, kStepTokens, kStepTokens)
     }
     while (s < plain_turns) KVC_TURN(false, s & 3, kStepTokens, kStepTokens)
-    while (s < wg_steps) KVC_TURN(true, s & 3, wave_vis - s * kStepTokens, my_pos + 1 - (s + 1) * kStepTokens)
+    // steps past the last token that any row of this wavefront sees carry no weight for it: it
+    // only loads and synchronises during the workgroup's remaining turns
+    const int live_turns = min(wg_steps, (wave_vis + kStepTokens - 1) / kStepTokens);
+    while (s < live_turns) KVC_TURN(true, s & 3, wave_vis - s * kStepTokens, my_pos + 1 - (s + 1) * kStepTokens)
+    for (; s < wg_steps; ++s) {
+        KVC_TURN_BEGIN(s & 3);
+        if (GROUPS == 2) phase_barrier();
+        turn_k();
+        turn_v();
+        KVC_TURN_END();
+    }
 #undef KVC_TURN
 #undef KVC_TURN_BEGIN
 #undef KVC_TURN_END
+    if (GROUPS == 2 && group == 0) phase_barrier();
     wait_loads_but<0>();  // nothing may still be landing in LDS when the workgroup's LDS is handed on
 
     // lane (half, c) holds O[query row i0 + r][head0 + (c >> 4)][32*b + 8*a + 4*half .. +3] in acc[b][4a .. 4a+3]
@@ -567,10 +630,20 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k_cache, const void 
     const auto *kk = static_cast<const uint16_t *>(k_cache);
     const auto *vv = static_cast<const uint16_t *>(v_cache);
     auto *oo = static_cast<uint16_t *>(out);
-    const unsigned grid = unsigned(int64_t(p.num_q_heads / 2) * p.num_seqs * p.max_query_tiles);
-    const dim3 g(grid), b(kThreads);
-    if (p.block_size < kTileTokens) pa_prefill_mfma32_kernel<true><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
-    else pa_prefill_mfma32_kernel<false><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p);
+    // Two groups per workgroup pay off when there are workgroups enough to keep every compute unit
+    // busy for several rounds; short launches keep the finer grain of 64-row workgroups.
+    const int64_t wide_grid = int64_t(p.num_q_heads / 2) * p.num_seqs * ((p.max_query_tiles + 1) / 2);
+    const bool wide = wide_grid >= 2 * 256;
+    const bool small = p.block_size < kTileTokens;
+    const int query_tiles = wide ? (p.max_query_tiles + 1) / 2 : p.max_query_tiles;  // max_query_tiles counts 64-row tiles
+    const dim3 g(unsigned(int64_t(p.num_q_heads / 2) * p.num_seqs * query_tiles)), b(wide ? 512 : 256);
+#define KVC_LAUNCH(SMALL, GROUPS) \
+    pa_prefill_mfma32_kernel<SMALL, GROUPS><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p, query_tiles)
+    if (wide && small) KVC_LAUNCH(true, 2);
+    else if (wide) KVC_LAUNCH(false, 2);
+    else if (small) KVC_LAUNCH(true, 1);
+    else KVC_LAUNCH(false, 1);
+#undef KVC_LAUNCH
     return hipGetLastError();
 }
 
