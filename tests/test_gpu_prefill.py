@@ -64,6 +64,17 @@ def test_small_tile_kernel_on_even_groups(oracle_mod, hq, hkv, bs):
     check(oracle_mod, w, q, qs, f"32x32 tiles {hq}/{hkv} bs={bs}", kernel=0)
 
 
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (4, 2)])
+def test_ragged_query_counts_in_wide_and_narrow_workgroups(oracle_mod, hq, hkv):
+    """32 / 8 heads with 12 sequences and up to 300 query rows make 576 workgroups of 128 query rows (two
+    groups of wavefronts, the second group or single wavefronts of it without rows); 4 / 2 heads stay
+    below the threshold and run 64-row workgroups.  Chunked: query rows are the last Qn positions."""
+    lens = [130, 40, 64, 65, 127, 129, 200, 256, 300, 513, 97, 1000]
+    qlens = [130, 1, 64, 65, 127, 129, 200, 256, 300, 17, 96, 129]
+    w, q, qs = make(360 + hq, lens, qlens, hq, hkv)
+    check(oracle_mod, w, q, qs, f"ragged {hq}/{hkv}")
+
+
 def test_negative_scale_takes_the_small_tile_kernel(oracle_mod):
     """The 32x32-tile kernel takes its max over raw scores and needs a positive scale; any other
     scale is served by the 16x16-tile kernel."""
