@@ -630,10 +630,11 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k_cache, const void 
     const auto *kk = static_cast<const uint16_t *>(k_cache);
     const auto *vv = static_cast<const uint16_t *>(v_cache);
     auto *oo = static_cast<uint16_t *>(out);
-    // Two groups per workgroup pay off when there are workgroups enough to keep every compute unit
-    // busy for several rounds; short launches keep the finer grain of 64-row workgroups.
+    // Two groups per workgroup pay off (by a few percent) for long recomputations with workgroups
+    // enough to keep every compute unit busy for several rounds; up to about 2048 query rows per
+    // sequence the finer grain of 64-row workgroups wins, whatever the batch (measured).
     const int64_t wide_grid = int64_t(p.num_q_heads / 2) * p.num_seqs * ((p.max_query_tiles + 1) / 2);
-    const bool wide = wide_grid >= 2 * 256;
+    const bool wide = wide_grid >= 2 * 256 && p.max_query_tiles >= 48;
     const bool small = p.block_size < kTileTokens;
     const int query_tiles = wide ? (p.max_query_tiles + 1) / 2 : p.max_query_tiles;  // max_query_tiles counts 64-row tiles
     const dim3 g(unsigned(int64_t(p.num_q_heads / 2) * p.num_seqs * query_tiles)), b(wide ? 512 : 256);

@@ -65,14 +65,32 @@ def test_small_tile_kernel_on_even_groups(oracle_mod, hq, hkv, bs):
 
 
 @pytest.mark.parametrize("hq,hkv", [(32, 8), (4, 2)])
-def test_ragged_query_counts_in_wide_and_narrow_workgroups(oracle_mod, hq, hkv):
-    """32 / 8 heads with 12 sequences and up to 300 query rows make 576 workgroups of 128 query rows (two
-    groups of wavefronts, the second group or single wavefronts of it without rows); 4 / 2 heads stay
-    below the threshold and run 64-row workgroups.  Chunked: query rows are the last Qn positions."""
+def test_ragged_query_counts(oracle_mod, hq, hkv):
+    """Chunked: query rows are the last Qn positions; counts around the 16-row, 64-row and 128-row
+    boundaries of the kernels' wavefronts and workgroups."""
     lens = [130, 40, 64, 65, 127, 129, 200, 256, 300, 513, 97, 1000]
     qlens = [130, 1, 64, 65, 127, 129, 200, 256, 300, 17, 96, 129]
     w, q, qs = make(360 + hq, lens, qlens, hq, hkv)
     check(oracle_mod, w, q, qs, f"ragged {hq}/{hkv}")
+
+
+def test_long_ragged_recompute_in_128_row_workgroups(oracle_mod):
+    """From 3072 query rows per sequence on (and 512 workgroups or more) a workgroup is two groups of
+    four wavefronts and 128 query rows: 3100 and 3073 rows leave the last workgroup with 28 rows (two
+    wavefronts of the first group) and with 1 row; sampled rows against the oracle's decode over the
+    truncated context."""
+    lens, qlens = [3100, 3300], [3100, 3073]
+    w, q, qs = make(370, lens, qlens, 32, 8)
+    got = out_to_f64(run(w, q, qs, 3100))
+    rng = np.random.default_rng(2)
+    for n in range(2):
+        first = lens[n] - qlens[n]
+        for i in [0, 15, 16, 63, 64, 127, 128, qlens[n] - 29, qlens[n] - 1] + rng.integers(0, qlens[n], 6).tolist():
+            pos = first + i
+            tbl = w.block_tables[n:n + 1]
+            ref = oracle_mod.paged_attention_decode(q[qs[n] + i:qs[n] + i + 1], w.k_cache, w.v_cache, tbl,
+                                                    np.array([pos + 1], dtype=np.int32), w.scale, dtype="bf16")
+            assert np.abs(got[qs[n] + i] - ref[0]).max() <= BF16_TOL, (n, i)
 
 
 def test_negative_scale_takes_the_small_tile_kernel(oracle_mod):
