@@ -74,6 +74,14 @@ def test_ragged_query_counts(oracle_mod, hq, hkv):
     check(oracle_mod, w, q, qs, f"ragged {hq}/{hkv}")
 
 
+@pytest.mark.parametrize("bs", [64, 128, 256])
+def test_blocks_of_several_tiles(oracle_mod, bs):
+    """Blocks of 4, 8 and 16 tiles of 16 tokens: a wavefront's tile of a step is a sub-tile of a block."""
+    lens = [1, 17, 63, 64, 65, 250, 256, 257, 700]
+    w, q, qs = make(380 + bs, lens, lens, 8, 2, bs=bs)
+    check(oracle_mod, w, q, qs, f"bs={bs}")
+
+
 def test_long_ragged_recompute_in_128_row_workgroups(oracle_mod):
     """From 3072 query rows per sequence on (and 512 workgroups or more) a workgroup is two groups of
     four wavefronts and 128 query rows: 3100 and 3073 rows leave the last workgroup with 28 rows (two
