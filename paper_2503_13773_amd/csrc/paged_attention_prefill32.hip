@@ -11,10 +11,11 @@
 // tiles that adds up to about 800 port cycles against 544 matrix cycles; with 16 large tiles it
 // is about 500 port cycles against 512.
 //
-// One workgroup = (sequence, 2 query heads sharing one KV head, 64 consecutive query rows);
-// each of its 4 wavefronts owns 16 query rows x 2 heads = the 32 columns of its tiles (column
-// c = 16 * head + row).  The workgroup walks the context in steps of 32 tokens (the 32 rows of
-// a score tile), one barrier per step.
+// One workgroup = (sequence, 2 query heads sharing one KV head, 64 or 128 consecutive query
+// rows); each of its 4 or 8 wavefronts owns 16 query rows x 2 heads = the 32 columns of its
+// tiles (column c = 16 * head + row).  The workgroup walks the context in steps of 32 tokens
+// (the 32 rows of a score tile).  With 8 wavefronts the two groups of four run half a turn
+// apart, so that the two wavefronts of a SIMD are in opposite halves of their turns.
 //
 // K and V rows travel from the cache straight into LDS (global_load_lds_dwordx4: lane l of a
 // wavefront writes its 16 bytes at M0 + 16 * l, no register staging), requested two turns
