@@ -235,7 +235,7 @@ __device__ inline void phase_barrier() {
 //                       reads K operand 4 + j of step next
 //     chunks  4 ..  7   O block b += V slice 0 . weights 0..7   2 weights each (scores 8 .. 15), rounding, sum
 //                       reads V operand b, slice 1, of step cur
-//     chunks  8 .. 11   S(next) += K operand j . Q, j >= 4
+//     chunks  8 .. 11   S(next) += K operand j . Q, j >= 4      block id of the following turn's loads (`lookup`)
 //                       reads K operand j - 4 of the step after next and V operand j - 4, slice 0, of step next
 //     chunks 12 .. 15   O block b += V slice 1 . weights 8..15  max of S(next)
 //                       requests the K and V rows of the step four ahead (`issue_k`, `issue_v`)
@@ -244,12 +244,12 @@ __device__ inline void phase_barrier() {
 // On return x holds the raw scores of step `next` and the reference point is rebased for it.
 // MASKED: `vlim_cur` = tokens of step cur visible to any column of this wavefront,
 // `limit_next` = tokens of step next visible to this lane's column.
-template <bool MASKED, class IssueK, class IssueV, class Mid>
+template <bool MASKED, class IssueK, class IssueV, class Mid, class Lookup>
 __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&ka_lo)[4], uint2 (&va0)[4][2],
                                      const unsigned char *krow1, const unsigned char *krow2,
                                      const unsigned char *sv_cur, const unsigned char *sv_next, const int (&voff)[4],
                                      const bf16x8 (&qb)[8], float scale_log2e, int vlim_cur, int limit_next, int half,
-                                     int c, const IssueK &issue_k, const IssueV &issue_v, const Mid &mid) {
+                                     int c, const IssueK &issue_k, const IssueV &issue_v, const Mid &mid, const Lookup &lookup) {
     const float neg_m = -st.m;
     float arg[16], pf[16], pair[8];
     uint32_t w[8];
@@ -308,6 +308,7 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
     mid();  // the workgroup's half-turn barrier: the other group of wavefronts changes phase here too
     KVC_PIN();
 
+    lookup();  // block id for the loads of the next turn: half a turn for the scalar load to return
     KVC_QK_HI(0); KVC_ROUND(7); KVC_SUM(6);
     KVC_PIN();
     const uint4 pw1 = {w[4], w[5], w[6], w[7]};
@@ -511,8 +512,8 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     auto turn_v = [&]() __attribute__((always_inline)) {                                          \
         issue_v((ph + 3) & 3, src_v, idv);                                                        \
         ids_v = idk;                                                                              \
-        ids_k = ids_of(min(s + 5, wg_steps - 1));                                                 \
-    }
+    };                                                                                            \
+    auto turn_lookup = [&]() __attribute__((always_inline)) { ids_k = ids_of(min(s + 5, wg_steps - 1)); }
 #define KVC_TURN_END()     \
     wait_loads_but<2 * kLoads>();   \
     turn_barrier()
@@ -526,6 +527,7 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
         for (; s < wg_steps; ++s) {
             KVC_TURN_BEGIN(s & 3);
             if (GROUPS == 2) phase_barrier();
+            turn_lookup();
             turn_k();
             turn_v();
             KVC_TURN_END();
@@ -575,7 +577,7 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
         pipeline_turn<MASKED>(st, x, ka_lo, va0, k_lane + ((ph + 1) & 3) * kStageBytes,                        \
                               k_lane + ((ph + 2) & 3) * kStageBytes, v_base + ph * kStageBytes,                \
                               v_base + ((ph + 1) & 3) * kStageBytes, voff, qb, p.scale_log2e, VLIM, LIMIT,     \
-                              half, c, turn_k, turn_v, mid);                                                   \
+                              half, c, turn_k, turn_v, mid, turn_lookup);                                      \
         KVC_TURN_END();                                                                                        \
         ++s;                                                                                                   \
     }
@@ -594,6 +596,7 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     for (; s < wg_steps; ++s) {
         KVC_TURN_BEGIN(s & 3);
         if (GROUPS == 2) phase_barrier();
+        turn_lookup();
         turn_k();
         turn_v();
         KVC_TURN_END();
