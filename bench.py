@@ -47,6 +47,61 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def recompute_attention_detail(args, log):
+    """The recompute path (paged causal prefill, the same 8B-shape heads) beside the step: causal attention
+    of one preempted request of S tokens over its block list, best of 3 x 5 back-to-back launches, against
+    the 2.5 PFLOP/s dense bf16 matrix-core peak; sampled rows are checked against the oracle first.
+    Not part of `value`."""
+    import math
+    import numpy as np
+    import torch
+    import kvc_workloads as W
+    import paper_2503_13773_amd as K
+    hq, hkv, d, bs = 32, 8, 128, 16
+    out = {}
+    for S in (2048, 4096, 16384):
+        rng = np.random.default_rng(7000 + S)
+        lens = np.array([S], dtype=np.int32)
+        nblk = int(W.blocks_needed(lens, bs).max())
+        w = W.build_workload("recompute", rng, dtype=W.BF16, context_lens=lens, num_q_heads=hq, num_kv_heads=hkv,
+                             head_dim=d, block_size=bs, max_blocks_per_seq=nblk + 1, num_pool_blocks=nblk + 5)
+        q_np = W.f32_to_bf16_bits(rng.standard_normal((S, hq, d)).astype(np.float32))
+        q = torch.from_numpy(q_np.view(np.int16)).view(torch.bfloat16).cuda()
+        kc = torch.from_numpy(w.k_cache.view(np.int16)).view(torch.bfloat16).cuda()
+        vc = torch.from_numpy(w.v_cache.view(np.int16)).view(torch.bfloat16).cuda()
+        tbl = torch.from_numpy(w.block_tables).cuda()
+        ln = torch.from_numpy(w.context_lens).cuda()
+        qs = torch.tensor([0, S], dtype=torch.int32).cuda()
+        res = torch.empty_like(q)
+        K.paged_attention_prefill(q, kc, vc, tbl, ln, qs, w.scale, S, res)
+        torch.cuda.synchronize()
+        if not args.no_check:
+            import oracle
+            got = res.float().cpu().numpy().astype(np.float64)
+            for pos in (0, 17, S // 2 + 3, S - 1):
+                ref = oracle.paged_attention_decode(q_np[pos:pos + 1], w.k_cache, w.v_cache, w.block_tables,
+                                                    np.array([pos + 1], dtype=np.int32), w.scale, dtype="bf16")
+                err = float(np.abs(got[pos] - ref[0]).max())
+                if not err <= 2e-2:
+                    log(f"[bench] recompute attention S={S}: row {pos} differs from the oracle by {err:.3e}")
+                    raise SystemExit(4)
+        best = float("inf")
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                K.paged_attention_prefill(q, kc, vc, tbl, ln, qs, w.scale, S, res)
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) / 5)
+        flops = 4.0 * d * hq * S * (S + 1) / 2
+        out[str(S)] = {"us": round(best * 1e3, 1), "TFLOPs": round(flops / best / 1e9, 1),
+                       "frac_of_mfma_peak": round(flops / best / 1e9 / 2500.0, 4)}
+    log("[bench] recompute attention (one request, per layer): " +
+        ", ".join(f"S={k}: {v['us']} us = {v['TFLOPs']} TFLOP/s ({100 * v['frac_of_mfma_peak']:.1f} %)" for k, v in out.items()))
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +117,8 @@ def main() -> int:
     ap.add_argument("--swap-frac", type=float, default=0.20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the oracle check before timing (A/B timing runs)")
+    ap.add_argument("--no-recompute", action="store_true",
+                    help="skip the recompute (paged causal prefill) timing that goes into detail.recompute_attention")
     ap.add_argument("--cpu-threads", type=int, default=0)
     args = ap.parse_args()
 
@@ -325,6 +382,8 @@ def main() -> int:
         except Exception:
             traffic = None
 
+    recompute = None if args.no_recompute else recompute_attention_detail(args, log)
+
     part_bytes = attn_bytes  # what one launch of the attention kernel must move (K+V once, q, out; partials not counted)
     achieved = part_bytes / part_avg / 1e9
     value = step_bytes / step_s / 1e9
@@ -359,6 +418,7 @@ def main() -> int:
             "attention_scheduled_pct_of_peak_back_to_back":
                 None if sched_region is None else round(100.0 * attn_bytes / sched_region / 1e9 / HBM_PEAK_GBS, 2),
             "schedule_build_us": None if sched_build is None else round(sched_build * 1e6, 2),
+            "recompute_attention": recompute,
         },
         "roofline": {"bound": "hbm", "kernel": {1: "pa_partial_valu_kernel", 2: "pa_partial_mfma_kernel", 3: "pa_partial_mfma_kernel", 4: "pa_stream_mfma_kernel"}[int(plan.kernel)],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
