@@ -239,8 +239,9 @@ KVC_API int kvc_validate_attention_inputs(const int32_t *block_tables, const int
  *                 the launch grid; rows of sequences with Qn > max_query_len beyond it are not
  *                 computed).
  * Every shape the descriptor allows is served: bf16 with head_dim 128 and group <= 16 runs on
- * the matrix cores (any block size): on 32x32 tiles when the group size is even and the scale
- * positive, on 16x16 tiles otherwise or when desc->kernel is KVC_KERNEL_MFMA; everything else
+ * the matrix cores (any block size): on 32x32 tiles when the scale is positive (two heads of a KV
+ * head per wavefront for even group sizes, one head otherwise), on 16x16 tiles for other scales or
+ * when desc->kernel is KVC_KERNEL_MFMA; everything else
  * (fp32, head_dim 64, larger groups) on the vector ALUs, one workgroup per query row and head
  * chunk.  No workspace.  desc->max_context_len and partition_tokens are ignored; desc->kernel must
  * be valid for the shape and is otherwise ignored.

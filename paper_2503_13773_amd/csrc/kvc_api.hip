@@ -547,9 +547,9 @@ int kvc_paged_attention_prefill(const void *q, const void *k_cache, const void *
     p.scale_log2e = float(double(scale) * 1.4426950408889634);
     if (int64_t(p.num_q_heads / p.heads_per_chunk) * p.num_seqs * p.max_query_tiles > kMaxGrid)
         return KVC_ERR_BAD_SHAPE;
-    // 32x32 tiles need two heads of one KV head per wavefront and a positive scale (their max is
-    // taken over raw scores); KVC_KERNEL_MFMA asks for the 16x16-tile kernel whatever the shape
-    const bool tiles32 = p.heads_per_chunk == 2 && p.scale_log2e > 0.0f && desc->kernel != KVC_KERNEL_MFMA;
+    // 32x32 tiles need a positive scale (their max is taken over raw scores); KVC_KERNEL_MFMA asks
+    // for the 16x16-tile kernel whatever the shape
+    const bool tiles32 = p.scale_log2e > 0.0f && desc->kernel != KVC_KERNEL_MFMA;
     const hipError_t e = tiles32 ? kvc::launch_prefill_mfma32(q, k_cache, v_cache, block_tables, context_lens, q_start,
                                                               out, p, static_cast<hipStream_t>(hip_stream))
                                  : kvc::launch_prefill_mfma(q, k_cache, v_cache, block_tables, context_lens, q_start,

@@ -1,5 +1,5 @@
 // Causal attention of many query positions per sequence over the block-allocated KV cache on
-// 32x32x16 matrix-core tiles (gfx950, bf16, head_dim 128, even GQA group sizes): the
+// 32x32x16 matrix-core tiles (gfx950, bf16, head_dim 128, positive scale): the
 // recomputation path of a preempted request (prefill re-run over prompt + generated tokens,
 // quadratic in the sequence length: paper Section 2.5 and 3.5) and chunked prefill.
 //
@@ -13,7 +13,9 @@
 //
 // One workgroup = (sequence, 2 query heads sharing one KV head, 64 or 128 consecutive query
 // rows); each of its 4 or 8 wavefronts owns 16 query rows x 2 heads = the 32 columns of its
-// tiles (column c = 16 * head + row).  The workgroup walks the context in steps of 32 tokens
+// tiles (column c = 16 * head + row).  Odd GQA group sizes take one head and 32 query rows per
+// wavefront instead (workgroups of 128 or 256 rows); everything below is written for two heads
+// and holds for one with "row" = c.  The workgroup walks the context in steps of 32 tokens
 // (the 32 rows of a score tile).  With 8 wavefronts the two groups of four run half a turn
 // apart, so that the two wavefronts of a SIMD are in opposite halves of their turns.
 //
@@ -354,10 +356,11 @@ __device__ inline void pipeline_turn(ColumnState &st, float (&x)[16], bf16x8 (&k
 #undef KVC_PV1
 }
 
-// GROUPS = 1: workgroups of four wavefronts (64 query rows), two per compute unit.  GROUPS = 2:
-// workgroups of two groups of four wavefronts (128 query rows), one per compute unit; the groups
-// run half a turn apart (see below).  Either way a SIMD holds two wavefronts.
-template <bool SMALL, int GROUPS>
+// HEADS = 2: the 32 columns of a wavefront are 16 query rows x 2 heads of one KV head (even GQA
+// groups); HEADS = 1: 32 query rows of one head.  GROUPS = 1: workgroups of four wavefronts, two
+// per compute unit.  GROUPS = 2: workgroups of two groups of four wavefronts, one per compute
+// unit; the groups run half a turn apart (see below).  Either way a SIMD holds two wavefronts.
+template <bool SMALL, int GROUPS, int HEADS>
 __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const int32_t *__restrict__ block_tables,
@@ -365,17 +368,18 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     uint16_t *__restrict__ out, PrefillParams p, int query_tiles) {
     __shared__ __attribute__((aligned(1024))) unsigned char s_k[kKStages][kStageBytes];
     __shared__ __attribute__((aligned(1024))) unsigned char s_v[kVStages][kStageBytes];
-    constexpr int kTileRows = 64 * GROUPS;          // query rows of a workgroup: 16 per wavefront
+    constexpr int kWaveRows = 32 / HEADS;           // query rows of a wavefront: column c = kWaveRows * head + row
+    constexpr int kTileRows = 4 * kWaveRows * GROUPS;  // query rows of a workgroup
     constexpr int kLoads = 2 / GROUPS;              // 1 KiB loads of K (and of V) per wavefront and step
     constexpr int kWavesPerTile = 2 * GROUPS;       // wavefronts that share a 16-row tile of a step
 
     // blockIdx.x = head pair + pairs * (seq + num_seqs * reversed query tile)
-    const int chunks = p.num_q_heads / 2;
+    const int chunks = p.num_q_heads / HEADS;
     const int item = blockIdx.x;
     const int chunk = item % chunks;
     const int n = (item / chunks) % p.num_seqs;
     const int qtile = query_tiles - 1 - item / (chunks * p.num_seqs);
-    const int head0 = chunk * 2;
+    const int head0 = chunk * HEADS;
     const int kvh = head0 / p.group;
 
     const int S = context_lens[n];
@@ -387,7 +391,8 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int group = wave >> 2;  // GROUPS = 2: wavefronts w and w + 4 share a SIMD; group 1 runs half a turn behind group 0
     const int half = lane >> 5, c = lane & 31;
-    const int r = c & 15;  // query row of the column inside the wavefront's 16; c >> 4 = its head
+    const int r = c % kWaveRows;  // query row of the column inside the wavefront's rows
+    const int my_head = head0 + c / kWaveRows;
 
     // tiles and steps this workgroup walks (up to the position of its last query row)
     const int last_pos = S - Qn + min(Qn, qtile * kTileRows + kTileRows) - 1;
@@ -396,9 +401,9 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     const int32_t *table = block_tables + size_t(n) * p.max_blocks_per_seq;
 
     // wavefronts past the last query row still load and synchronise, they just never compute
-    const int i0 = qtile * kTileRows + 16 * wave;  // first query row of this wavefront
+    const int i0 = qtile * kTileRows + kWaveRows * wave;  // first query row of this wavefront
     const bool active = i0 < Qn;
-    const int nrows = active ? min(16, Qn - i0) : 1;
+    const int nrows = active ? min(kWaveRows, Qn - i0) : 1;
     const int row = min(r, nrows - 1);      // lanes past the last query row shadow it
     const int p0 = S - Qn + (active ? i0 : 0);  // position of row 0
     const int my_pos = p0 + row;
@@ -407,7 +412,7 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
 
     bf16x8 qb[8];
     {
-        const uint16_t *qrow = q + (size_t(qs + (active ? i0 : 0) + row) * p.num_q_heads + head0 + (c >> 4)) * D + 8 * half;
+        const uint16_t *qrow = q + (size_t(qs + (active ? i0 : 0) + row) * p.num_q_heads + my_head) * D + 8 * half;
 #pragma unroll
         for (int j = 0; j < 8; ++j) qb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qrow + 16 * j));
     }
@@ -607,10 +612,10 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
     if (GROUPS == 2 && group == 0) phase_barrier();
     wait_loads_but<0>();  // nothing may still be landing in LDS when the workgroup's LDS is handed on
 
-    // lane (half, c) holds O[query row i0 + r][head0 + (c >> 4)][32*b + 8*a + 4*half .. +3] in acc[b][4a .. 4a+3]
+    // lane (half, c) holds O[query row i0 + r][my_head][32*b + 8*a + 4*half .. +3] in acc[b][4a .. 4a+3]
     const float inv = 1.0f / sum_over_halves(st.lsum);
     if (r < nrows) {
-        uint16_t *dst = out + (size_t(qs + i0 + r) * p.num_q_heads + head0 + (c >> 4)) * D + 4 * half;
+        uint16_t *dst = out + (size_t(qs + i0 + r) * p.num_q_heads + my_head) * D + 4 * half;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -625,7 +630,8 @@ __global__ __launch_bounds__(256 * GROUPS, 3 - GROUPS) void pa_prefill_mfma32_ke
 
 }  // namespace
 
-// Needs an even group size and a positive scale (the max is taken over raw scores).
+// Needs a positive scale (the max is taken over raw scores).  heads_per_chunk = 2: two heads of a
+// KV head per wavefront (even group sizes); 1: one head, twice the query rows.
 hipError_t launch_prefill_mfma32(const void *q, const void *k_cache, const void *v_cache,
                                  const int32_t *block_tables, const int32_t *context_lens,
                                  const int32_t *q_start, void *out, const PrefillParams &p,
@@ -634,20 +640,30 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k_cache, const void 
     const auto *kk = static_cast<const uint16_t *>(k_cache);
     const auto *vv = static_cast<const uint16_t *>(v_cache);
     auto *oo = static_cast<uint16_t *>(out);
+    const int heads = p.heads_per_chunk;
+    const int rows64 = 2 / heads;  // 64-row units in the query rows of four wavefronts
     // Two groups per workgroup pay off (by a few percent) for long recomputations with workgroups
     // enough to keep every compute unit busy for several rounds; up to about 2048 query rows per
-    // sequence the finer grain of 64-row workgroups wins, whatever the batch (measured).
-    const int64_t wide_grid = int64_t(p.num_q_heads / 2) * p.num_seqs * ((p.max_query_tiles + 1) / 2);
+    // sequence the finer grain of four-wavefront workgroups wins, whatever the batch (measured).
+    const auto tiles_of = [&](int groups) { return (p.max_query_tiles + rows64 * groups - 1) / (rows64 * groups); };
+    const int64_t wide_grid = int64_t(p.num_q_heads / heads) * p.num_seqs * tiles_of(2);
     const bool wide = wide_grid >= 2 * 256 && p.max_query_tiles >= 48;
     const bool small = p.block_size < kTileTokens;
-    const int query_tiles = wide ? (p.max_query_tiles + 1) / 2 : p.max_query_tiles;  // max_query_tiles counts 64-row tiles
-    const dim3 g(unsigned(int64_t(p.num_q_heads / 2) * p.num_seqs * query_tiles)), b(wide ? 512 : 256);
-#define KVC_LAUNCH(SMALL, GROUPS) \
-    pa_prefill_mfma32_kernel<SMALL, GROUPS><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, q_start, oo, p, query_tiles)
-    if (wide && small) KVC_LAUNCH(true, 2);
-    else if (wide) KVC_LAUNCH(false, 2);
-    else if (small) KVC_LAUNCH(true, 1);
-    else KVC_LAUNCH(false, 1);
+    const int query_tiles = tiles_of(wide ? 2 : 1);  // max_query_tiles counts 64-row tiles
+    const dim3 g(unsigned(int64_t(p.num_q_heads / heads) * p.num_seqs * query_tiles)), b(wide ? 512 : 256);
+#define KVC_LAUNCH(SMALL, GROUPS, HEADS)                                                                        \
+    pa_prefill_mfma32_kernel<SMALL, GROUPS, HEADS><<<g, b, 0, stream>>>(qq, kk, vv, block_tables, context_lens, \
+                                                                         q_start, oo, p, query_tiles)
+#define KVC_LAUNCH_HEADS(SMALL, GROUPS)           \
+    do {                                          \
+        if (heads == 2) KVC_LAUNCH(SMALL, GROUPS, 2); \
+        else KVC_LAUNCH(SMALL, GROUPS, 1);        \
+    } while (0)
+    if (wide && small) KVC_LAUNCH_HEADS(true, 2);
+    else if (wide) KVC_LAUNCH_HEADS(false, 2);
+    else if (small) KVC_LAUNCH_HEADS(true, 1);
+    else KVC_LAUNCH_HEADS(false, 1);
+#undef KVC_LAUNCH_HEADS
 #undef KVC_LAUNCH
     return hipGetLastError();
 }

@@ -54,10 +54,11 @@ def test_full_recompute_matches_oracle(oracle_mod, hq, hkv):
     check(oracle_mod, w, q, qs, f"recompute {hq}/{hkv}")
 
 
-@pytest.mark.parametrize("hq,hkv,bs", [(4, 1, 16), (8, 2, 32), (32, 8, 16)])
-def test_small_tile_kernel_on_even_groups(oracle_mod, hq, hkv, bs):
-    """kernel = 2 (KVC_KERNEL_MFMA) asks for the 16x16-tile kernel where the default takes 32x32 tiles:
-    both against the oracle on the same input, and within rounding of each other."""
+@pytest.mark.parametrize("hq,hkv,bs", [(4, 1, 16), (8, 2, 32), (32, 8, 16), (3, 1, 16), (4, 4, 16), (5, 1, 32)])
+def test_both_tile_kernels(oracle_mod, hq, hkv, bs):
+    """kernel = 2 (KVC_KERNEL_MFMA) asks for the 16x16-tile kernel where the default takes 32x32 tiles (two
+    heads per wavefront for even group sizes, one head and 32 query rows for odd ones): both against the
+    oracle on the same input."""
     lens = [1, 5, 16, 17, 63, 64, 65, 130, 300, 1000]
     w, q, qs = make(340 + hq + bs, lens, lens, hq, hkv, bs=bs)
     check(oracle_mod, w, q, qs, f"16x16 tiles {hq}/{hkv} bs={bs}", kernel=2)
