@@ -27,9 +27,14 @@ def causal_attention_flops(S: int, q_heads: int, head_dim: int) -> float:
 
 def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int = 32, kv_heads: int = 8,
                       head_dim: int = 128, block_size: int = 16, reps: int = 5, seed: int = 0,
-                      fit_from: int = 2048, batch: int = 1) -> Dict:
+                      fit_from: int = 2048, batch: int = 1, settle_ms: float = 30.0, timed_ms: float = 20.0) -> Dict:
     """Time the causal attention of `batch` requests of S tokens each (recomputed in one launch,
-    every request with a block list of its own) for every S in seq_lens."""
+    every request with a block list of its own) for every S in seq_lens.  Each length is launched
+    back to back for `settle_ms` first (after an idle spell the device's clocks need 10-20 ms of
+    work to settle; a recomputation runs one such launch per layer, so the settled rate is the
+    one that counts), then timed over at least `reps` launches and about `timed_ms`."""
+    import time
+
     import torch
 
     from . import binding as K
@@ -51,16 +56,22 @@ def profile_recompute(seq_lens: Sequence[int], *, layers: int = 32, q_heads: int
         qs = (torch.arange(batch + 1, dtype=torch.int32) * S).cuda()
         out = torch.empty_like(q)
         scale = 1.0 / math.sqrt(head_dim)
+        fl = causal_attention_flops(S, q_heads, head_dim) * batch
         K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
+        t_end = time.perf_counter() + settle_ms * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(8):
+                K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
+            torch.cuda.synchronize()
+        n = max(reps, int(timed_ms * 1e-3 / (fl / 1.0e15)))
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record(stream)
-        for _ in range(reps):
+        for _ in range(n):
             K.paged_attention_prefill(q, k_cache, v_cache, table, lens, qs, scale, S, out)
         b.record(stream)
         torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / reps
-        fl = causal_attention_flops(S, q_heads, head_dim) * batch
+        ms = a.elapsed_time(b) / n
         samples.append({"S": int(S), "batch": int(batch), "layer_ms": ms, "all_layers_ms": ms * layers,
                         "tflops": fl / ms / 1e9, "frac_of_mfma_peak": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS})
     fit = [s for s in samples if s["S"] >= fit_from] if sum(s["S"] >= fit_from for s in samples) >= 2 else samples
@@ -93,14 +104,15 @@ def main() -> int:
     ap.add_argument("--q-heads", type=int, default=32)
     ap.add_argument("--kv-heads", type=int, default=8)
     ap.add_argument("--seq-lens", type=int, nargs="+", default=[256, 512, 1024, 2048, 4096, 8192, 16384])
-    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--reps", type=int, default=5, help="least number of timed launches per length")
+    ap.add_argument("--settle-ms", type=float, default=30.0, help="untimed back-to-back launches before each length")
     ap.add_argument("--batch", type=int, default=1, help="requests of S tokens recomputed in one launch")
     ap.add_argument("--markdown", action="store_true", help="print a table instead of JSON")
     ap.add_argument("--swap-gamma-ms", type=float, default=0.004744, help="slope of the swap regressor (ms per token)")
     ap.add_argument("--swap-delta-ms", type=float, default=0.145, help="offset of the swap regressor (ms)")
     args = ap.parse_args()
     res = profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads, kv_heads=args.kv_heads,
-                            reps=args.reps, batch=args.batch)
+                            reps=args.reps, batch=args.batch, settle_ms=args.settle_ms)
     print(markdown(res, args.swap_gamma_ms, args.swap_delta_ms) if args.markdown else json.dumps(res))
     return 0
 
