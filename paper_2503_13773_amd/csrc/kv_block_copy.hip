@@ -4,11 +4,14 @@
 // (paper Section 2.5 and 3.5: cost linear in the sequence length) and behind
 // relocating blocks when allocated-but-unused KV cache is reused (Section 3.3.1).
 //
-// Pure HBM streaming: every lane moves 16-byte words; a workgroup of 256 lanes
-// moves a contiguous 16 KiB slab of one (pair, plane) block as four independent
-// 4 KiB rounds, all loads issued before the first store so that 64 bytes per
-// lane are in flight.  The (src, dst) pair is read once per workgroup through
-// the scalar path (its index is workgroup-uniform).
+// Pure HBM streaming: a workgroup is one wavefront that moves one contiguous 1 KiB
+// slab of one (pair, plane) block, a 16-byte non-temporal load and store per lane.
+// Many small workgroups beat fewer, larger ones here (measured on the cfg3b swap-out,
+// 51 MB each way: 18.5 us against 19.0 us with 256 lanes x 16 bytes, 19.7 us with 256
+// lanes x 64 bytes, 31.5 us with one workgroup per 32 KiB block, 20.5 us and more for
+// grid-stride loops with the next load in flight): the device keeps more independent
+// wavefronts in flight and the tail of the grid is finer.  The (src, dst) pair is read
+// once per workgroup through the scalar path (its index is workgroup-uniform).
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -17,8 +20,10 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte word
 
-constexpr int kRounds = 4;                            // 16-byte words per lane
-constexpr int64_t kSlabBytes = int64_t(kThreads) * 16 * kRounds;  // 16 KiB per workgroup
+constexpr int kCopyThreads = 64;                      // one wavefront per workgroup
+constexpr int kRounds = 1;                            // 16-byte words per lane
+constexpr int64_t kSlabBytes = kCopySlabBytes;          // 1 KiB per workgroup
+static_assert(kSlabBytes == int64_t(kCopyThreads) * 16 * kRounds, "slab = lanes x 16 bytes x rounds");
 
 struct CopyParams {
     const uint8_t *src;
@@ -30,7 +35,7 @@ struct CopyParams {
     int32_t slabs_per_block;
 };
 
-__global__ __launch_bounds__(kThreads) void kv_block_copy_kernel(CopyParams p,
+__global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(CopyParams p,
                                                                  const int64_t *__restrict__ mapping) {
     // grid.x = slab + slabs_per_block * pair, grid.y = plane
     const int64_t wg = blockIdx.x;
@@ -46,12 +51,12 @@ __global__ __launch_bounds__(kThreads) void kv_block_copy_kernel(CopyParams p,
     u32x4 w[kRounds];
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
-        const int64_t off = off0 + int64_t(r) * kThreads * 16;
+        const int64_t off = off0 + int64_t(r) * kCopyThreads * 16;
         if (off < p.block_bytes) w[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + off));
     }
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
-        const int64_t off = off0 + int64_t(r) * kThreads * 16;
+        const int64_t off = off0 + int64_t(r) * kCopyThreads * 16;
         if (off < p.block_bytes) __builtin_nontemporal_store(w[r], reinterpret_cast<u32x4 *>(d + off));
     }
 }
@@ -69,7 +74,7 @@ hipError_t launch_block_copy(const kvc_pool &src, const kvc_pool &dst, const int
     p.num_pairs = num_pairs;
     p.slabs_per_block = int32_t((src.block_bytes + kSlabBytes - 1) / kSlabBytes);
     const dim3 grid(unsigned(num_pairs * p.slabs_per_block), unsigned(src.num_planes), 1);
-    kv_block_copy_kernel<<<grid, dim3(kThreads), 0, stream>>>(p, mapping);
+    kv_block_copy_kernel<<<grid, dim3(kCopyThreads), 0, stream>>>(p, mapping);
     return hipGetLastError();
 }
 

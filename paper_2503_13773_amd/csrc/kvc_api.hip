@@ -291,7 +291,7 @@ int check_pools(const kvc_pool *src, const kvc_pool *dst, const int64_t *mapping
     if (num_pairs == 0) return KVC_OK;
     if (!src->base || !dst->base || !mapping) return KVC_ERR_NULL;
     if (!aligned16(src->base) || !aligned16(dst->base)) return KVC_ERR_ALIGN;
-    const int64_t slabs = ceil_div(src->block_bytes, int64_t(kvc::kThreads) * 64);
+    const int64_t slabs = ceil_div(src->block_bytes, kvc::kCopySlabBytes);
     if (num_pairs > kMaxGrid / slabs) return KVC_ERR_BAD_SHAPE;
     return KVC_OK;
 }

@@ -107,6 +107,7 @@ hipError_t launch_cache_append(const void *k_new, const void *v_new, void *k_cac
                                const int32_t *block_tables, const int32_t *positions, int num_seqs,
                                int num_kv_heads, int row_bytes, int block_size_log2,
                                int max_blocks_per_seq, hipStream_t stream);
+constexpr int64_t kCopySlabBytes = 1024;  // bytes one workgroup of the block-copy kernel moves (grid.x = pairs * slabs per block)
 hipError_t launch_block_copy(const kvc_pool &src, const kvc_pool &dst, const int64_t *mapping,
                              int64_t num_pairs, hipStream_t stream);
 
