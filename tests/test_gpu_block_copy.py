@@ -24,8 +24,10 @@ def gpu_copy(src_np, dst_np, mapping_np):
     (1, 128, 128, 32768, 8),          # cfg1-copy: 8 random blocks of 32 KiB
     (2, 64, 40, 32768, 17),
     (3, 50, 70, 16, 20),              # smallest legal block
-    (2, 33, 33, 4112, 33),            # not a multiple of the 4 KiB round
-    (4, 20, 20, 16384 + 48, 9),       # just over one slab
+    (2, 33, 33, 4112, 33),            # four 1 KiB slabs and one word
+    (4, 20, 20, 16384 + 48, 9),       # sixteen slabs and three words
+    (2, 12, 12, 1040, 7),             # just over one slab
+    (1, 12, 12, 1008, 5),             # just under one slab
     (64, 24, 24, 32768, 5),           # many planes (K,V x 32 layers)
     (1, 16, 16, 131072, 16),          # 7B-MHA block
 ])
