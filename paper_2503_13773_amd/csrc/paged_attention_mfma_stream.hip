@@ -687,8 +687,7 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
     // publications in the upper half.  If the worker's arrival was the last it merges, taking
     // its own piece from registers and polling for pieces that arrived but are not published
     // yet.  Otherwise it waits until its partial stores (device-scope accesses) have completed
-    // and adds 0x10000; the workgroup-scope release is that wait, and keeps the compiler from
-    // moving the stores.
+    // (an explicit wait on the vector memory counter) and adds 0x10000.
     if (h_cnt | t_cnt) {
         oh = uniform(oh);
         ot = uniform(ot);
@@ -696,7 +695,12 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         if ((h_cnt && !last_h) || (t_cnt && !last_t)) {
             if (h_cnt && !last_h) store_partial(2 * worker, hp);
             if (t_cnt && !last_t) store_partial(2 * worker + 1, st);
+            // The publication may become visible only after the partial has: wait until every
+            // store above has completed.  The fence alone does not do it (at workgroup scope
+            // it compiles to no wait at all on this target); it keeps the compiler from moving
+            // the stores.
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (lane == 0) {
                 if (h_cnt && !last_h) __hip_atomic_fetch_add(ws.cnt + h_j0, 0x10000, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (t_cnt && !last_t) __hip_atomic_fetch_add(ws.cnt + t_j0, 0x10000, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
