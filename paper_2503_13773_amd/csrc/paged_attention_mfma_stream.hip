@@ -138,11 +138,11 @@ __device__ inline float4 acc_vec(const mfma::HeadState &x, int v) {
 // 8 / PV times fewer loads in flight.  The worker's own partial comes from its registers
 // (`mine`, re-distributed through `lds`, >= 128 * G floats private to the wavefront, when
 // PV < 8): the same values its slot holds, so the result does not depend on which worker merges.
-template <int PV>
+template <int PV, typename Await>
 __device__ inline void merge_cut_rows(__amdgpu_buffer_rsrc_t acc_buf, __amdgpu_buffer_rsrc_t ml_buf,
                                       uint16_t *out, int G, int num_q_heads, int lane, float *lds,
                                       const CutRow (&row)[2], const mfma::HeadState &mine0,
-                                      const mfma::HeadState &mine1) {
+                                      const mfma::HeadState &mine1, Await await_row) {
     using namespace mfma;
     constexpr int HP = 2 * PV;  // heads a quad row of 16 lanes can carry: 4, 8 or 16
     const int quad = lane >> 4, r = lane & 15;
@@ -194,9 +194,14 @@ __device__ inline void merge_cut_rows(__amdgpu_buffer_rsrc_t acc_buf, __amdgpu_b
             }
         }
     };
+    // a row's pieces are fetched as soon as all of them are published: the other row's poll and
+    // the hand-over of the own pieces above run under the first row's loads
 #pragma unroll
     for (int w = 0; w < 2; ++w)
-        if (row[w].active) issue(w, 0);
+        if (row[w].active) {
+            await_row(w);
+            issue(w, 0);
+        }
 
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
@@ -591,15 +596,6 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         }                               // else: T piece, stays in `st`
     };
 
-    // Arrival at the cut rows: 1 is added to the lower half of their counter words.
-    int oh = 0, ot = 0;
-    auto arrive = [&]() __attribute__((always_inline)) {
-        if (lane == 0) {
-            if (h_cnt) oh = __hip_atomic_fetch_add(ws.cnt + h_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (t_cnt) ot = __hip_atomic_fetch_add(ws.cnt + t_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    };
-
     const uint32_t slots = 2u * gridDim.x * kWaves;
     const __amdgpu_buffer_rsrc_t acc_buf = raw_buffer(ws.acc, slots * uint32_t(G * D) * 4u);
     const __amdgpu_buffer_rsrc_t ml_buf = raw_buffer(ws.ml, slots * uint32_t(G) * 8u);
@@ -611,6 +607,15 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
                 store4_device_scope(acc_buf, slot_vec(slot, G, v, quad, r), f.x, f.y, f.z, f.w);
             }
             if (quad == 0) store2_device_scope(ml_buf, slot_ml(slot, G, r), x.m, x.l);
+        }
+    };
+
+    // Arrival at the cut rows: 1 is added to the lower half of their counter words.
+    int oh = 0, ot = 0;
+    auto arrive = [&]() __attribute__((always_inline)) {
+        if (lane == 0) {
+            if (h_cnt) oh = __hip_atomic_fetch_add(ws.cnt + h_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t_cnt) ot = __hip_atomic_fetch_add(ws.cnt + t_j0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
@@ -708,13 +713,15 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         }
         if (last_t | last_h) {
             const CutRow rows[2] = {{last_t, t_n, t_kvh, t_j0, t_cnt, 0}, {last_h, h_n, h_kvh, h_j0, h_cnt, worker - h_j0}};
-            if (last_t) await_publications(t_j0, t_cnt, ot);
-            if (last_h) await_publications(h_j0, h_cnt, oh);
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            auto await_row = [&](int w) __attribute__((always_inline)) {
+                if (w == 0) await_publications(t_j0, t_cnt, ot);
+                else await_publications(h_j0, h_cnt, oh);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the fetches stay behind the poll
+            };
             float *lds = reinterpret_cast<float *>(&s_tile[wave][0]);  // the tile addresses are no longer needed
-            if (G <= 4) merge_cut_rows<2>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
-            else if (G <= 8) merge_cut_rows<4>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
-            else merge_cut_rows<8>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp);
+            if (G <= 4) merge_cut_rows<2>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp, await_row);
+            else if (G <= 8) merge_cut_rows<4>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp, await_row);
+            else merge_cut_rows<8>(acc_buf, ml_buf, out, G, p.num_q_heads, lane, lds, rows, st, hp, await_row);
             // every arrival and publication of these rows has happened: leave their counters at 0
             if (lane == 0) {
                 if (last_t) __hip_atomic_store(ws.cnt + t_j0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
