@@ -11,6 +11,9 @@ copy mapping are shared by the replicas, as they are shared by the layers of one
 
 Before anything is timed the step's results are checked: attention rows against the CPU
 oracle and the swapped-out blocks bit for bit; a mismatch ends the run with exit status 4.
+Every timed loop is preceded by 30 ms of the same launches, untimed (--clock-ramp-ms): after
+an idle spell the device runs its first 10-20 ms of work at lower clocks.  The W warm-up
+steps follow, then exactly K timed steps.
 
 Prints ONE JSON line: whole-step throughput in algorithmic GB/s, the roofline record of the
 dominant kernel (the attention kernel, timed per launch with HIP events on the launch
