@@ -108,8 +108,8 @@ def main() -> int:
     ap.add_argument("--settle-ms", type=float, default=30.0, help="untimed back-to-back launches before each length")
     ap.add_argument("--batch", type=int, default=1, help="requests of S tokens recomputed in one launch")
     ap.add_argument("--markdown", action="store_true", help="print a table instead of JSON")
-    ap.add_argument("--swap-gamma-ms", type=float, default=0.004744, help="slope of the swap regressor (ms per token)")
-    ap.add_argument("--swap-delta-ms", type=float, default=0.145, help="offset of the swap regressor (ms)")
+    ap.add_argument("--swap-gamma-ms", type=float, default=0.004766, help="slope of the swap regressor (ms per token)")
+    ap.add_argument("--swap-delta-ms", type=float, default=0.069, help="offset of the swap regressor (ms)")
     args = ap.parse_args()
     res = profile_recompute(args.seq_lens, layers=args.layers, q_heads=args.q_heads, kv_heads=args.kv_heads,
                             reps=args.reps, batch=args.batch, settle_ms=args.settle_ms)
