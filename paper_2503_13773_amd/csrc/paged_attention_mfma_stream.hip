@@ -425,10 +425,20 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
         h_n = word(6); h_kvh = word(7); h_j0 = word(8); h_cnt = word(9);
         t_n = word(10); t_kvh = word(11); t_j0 = word(12); t_cnt = word(13);
     } else {
-        int lo = 0, hi = nseq;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (uniform(s_pref[mid]) * Hkv <= f0) lo = mid; else hi = mid;
+        int lo = 0;
+        if (nseq <= 4 * 64) {  // every lane tests one entry: the table is sorted, so the count is the position
+            int below = 0;
+            for (int base = 0; base < nseq; base += 64) {
+                const int n = base + lane;
+                below += __popcll(__ballot(n < nseq && s_pref[min(n, nseq)] * Hkv <= f0));
+            }
+            lo = uniform(below) - 1;  // s_pref[0] = 0 is never above f0
+        } else {
+            int hi = nseq;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (uniform(s_pref[mid]) * Hkv <= f0) lo = mid; else hi = mid;
+            }
         }
         first.n = lo;
         first.pref = uniform(s_pref[lo]);
@@ -458,15 +468,26 @@ __global__ __launch_bounds__(kThreads, 1) void pa_stream_mfma_kernel(
             c = next_row(c);
             t0 = 0;
         }
+        // x / C for 0 <= x < 2^30 with a quotient below 2^16 (a worker index): the float product
+        // is off by less than one, so one correction step either way makes it exact - a handful
+        // of instructions against the forty of an integer division, four times, on the path
+        // every wavefront walks before it can request its first tile
+        const float inv_c = 1.0f / float(C);
+        auto div_c = [&](int x) __attribute__((always_inline)) {
+            int qt = int(float(x) * inv_c);
+            const int rem = x - qt * C;
+            qt += (rem >= C) - (rem < 0);
+            return qt;
+        };
         if (first_tile > 0) {
             const int row_f = first.pref * Hkv + first.kvh * (first.tiles + kRowCost);
-            h_n = first.n; h_kvh = first.kvh; h_j0 = row_f / C;
-            h_cnt = (row_f + first.tiles - 1) / C - h_j0 + 1;
+            h_n = first.n; h_kvh = first.kvh; h_j0 = div_c(row_f);
+            h_cnt = div_c(row_f + first.tiles - 1) - h_j0 + 1;
         }
         if (NT > 0 && last_t0 == 0 && last_end < last.tiles) {
             const int row_f = last.pref * Hkv + last.kvh * (last.tiles + kRowCost);
-            t_n = last.n; t_kvh = last.kvh; t_j0 = row_f / C;
-            t_cnt = (row_f + last.tiles - 1) / C - t_j0 + 1;
+            t_n = last.n; t_kvh = last.kvh; t_j0 = div_c(row_f);
+            t_cnt = div_c(row_f + last.tiles - 1) - t_j0 + 1;
         }
     }
     if (NT == 0) {  // the range covered cost units only; no row counts this worker
