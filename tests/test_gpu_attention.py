@@ -394,10 +394,12 @@ def test_runs_on_a_side_stream_and_validates_inputs():
     assert K.validate_attention_inputs(d["tables"], long, desc) == -8
 
 
-@pytest.mark.parametrize("nseq", [1100, 4096, 4200])
+@pytest.mark.parametrize("nseq", [63, 64, 65, 255, 256, 257, 1100, 4096, 4200])
 def test_large_batches_of_short_sequences(oracle_mod, nseq):
     """4096 sequences is the limit of the balanced kernel (its prefix sum lives in LDS), 4200 takes
-    the fixed-partition kernel; contexts of 0 to 80 tokens make every worker cross many rows."""
+    the fixed-partition kernel; contexts of 0 to 80 tokens make every worker cross many rows.  Up
+    to 256 sequences a worker is placed by a count over the prefix table, one entry per lane and
+    64 per pass (empty sequences are ties in that table), beyond that by a binary search."""
     import paper_2503_13773_amd as K
     rng = np.random.default_rng(500 + nseq)
     lens = rng.integers(0, 81, nseq).astype(np.int32)
